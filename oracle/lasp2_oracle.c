@@ -1,0 +1,425 @@
+/*
+ * CPU oracle for causal (unnormalised, identity-kernel) linear attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU path, is
+ * never called by it, and only tests, the smoke check and the bench's
+ * cpu_baseline leg may load it.
+ *
+ * Everything is fp64.  Tensors are [G][N][d] row-major, where G = B*H
+ * independent (batch, head) groups; d is the fastest axis.
+ *
+ * Packed variable-length input (LASP-2 paper, "Variable Length" paragraph of
+ * the Compatibility appendix; block-diagonal reading: no state crosses a
+ * document boundary): the N tokens of every group are cut into documents by
+ * `cu` (n_docs+1 monotone offsets, cu[0]=0, cu[n_docs]=N).  n_docs==1 with
+ * cu={0,N} is the ordinary single-sequence case.
+ *
+ * Three independent families are provided so they can be pinned against each
+ * other and against closed forms by the CPU tests:
+ *   *_def     : the token-level definition, LASP-2 paper Eq. (3)
+ *               o_s = sum_{i<=s} (q_s . k_i) v_i     (diagonal inclusive)
+ *               and its analytic gradient written as the same kind of
+ *               double sum (Algorithm "LASP-2 w/ Masking (Backward Pass)"
+ *               with a single chunk).
+ *   *_rec     : the recurrent form, Eq. (4):  M_s = M_{s-1} + k_s^T v_s,
+ *               o_s = q_s M_s, and the matching two-scan backward.
+ *   chunk_states / state_prefix / attn_*_chunked :
+ *               the steps of Algorithm "LASP-2 w/ Masking" and its backward,
+ *               in the paper's order, over an arbitrary partition of the
+ *               tokens into chunks.
+ *
+ * Readings of the paper used here:
+ *   - the mask Psi multiplies elementwise, so the entries the paper prints as
+ *     "-infinity" act as 0 (Eq. (3) sums over i <= s only);
+ *   - empty prefix M_{1:0} and empty suffix dM_{T+1:T} are zero matrices;
+ *   - no 1/sqrt(d) factor, no normaliser, no feature map (basic linear
+ *     attention).
+ */
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int lasp2_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static double dot(const double* a, const double* b, long d)
+{
+    double s = 0.0;
+    for (long c = 0; c < d; ++c) s += a[c] * b[c];
+    return s;
+}
+
+/* document index of every token: doc[i] = k  <=>  cu[k] <= i < cu[k+1] */
+static long* doc_ids(long N, const long* cu, long n_docs)
+{
+    long* doc = (long*)malloc(sizeof(long) * (size_t)(N > 0 ? N : 1));
+    for (long k = 0; k < n_docs; ++k)
+        for (long i = cu[k]; i < cu[k + 1]; ++i) doc[i] = k;
+    return doc;
+}
+
+/* ------------------------------------------------------------------ */
+/* Definition, Eq. (3): O[i,:] = sum_{j<=i, doc(j)=doc(i)} (q_i.k_j) v_j */
+/* ------------------------------------------------------------------ */
+void lasp2_oracle_fwd_def(const double* Q, const double* K, const double* V,
+                          double* O, long G, long N, long d,
+                          const long* cu, long n_docs)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            const double* q = Q + (g * N + i) * d;
+            double* o = O + (g * N + i) * d;
+            for (long c = 0; c < d; ++c) o[c] = 0.0;
+            for (long j = cu[doc[i]]; j <= i; ++j) {
+                double s = dot(q, K + (g * N + j) * d, d);
+                const double* v = V + (g * N + j) * d;
+                for (long c = 0; c < d; ++c) o[c] += s * v[c];
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Gradient of <dO, O> under the definition.  With S_ij = q_i.k_j and
+ * G_ij = dO_i.v_j on the allowed pairs (j <= i, same document):
+ *   dQ[i,:] = sum_{j<=i} G_ij k_j
+ *   dK[j,:] = sum_{i>=j} G_ij q_i
+ *   dV[j,:] = sum_{i>=j} S_ij dO_i
+ * (backward algorithm with masking, taken with one chunk per document).
+ */
+void lasp2_oracle_bwd_def(const double* Q, const double* K, const double* V,
+                          const double* dO, double* dQ, double* dK, double* dV,
+                          long G, long N, long d, const long* cu, long n_docs)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            const double* go = dO + (g * N + i) * d;
+            double* dq = dQ + (g * N + i) * d;
+            for (long c = 0; c < d; ++c) dq[c] = 0.0;
+            for (long j = cu[doc[i]]; j <= i; ++j) {
+                double gij = dot(go, V + (g * N + j) * d, d);
+                const double* k = K + (g * N + j) * d;
+                for (long c = 0; c < d; ++c) dq[c] += gij * k[c];
+            }
+        }
+    }
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long j = 0; j < N; ++j) {
+            const double* k = K + (g * N + j) * d;
+            const double* v = V + (g * N + j) * d;
+            double* dk = dK + (g * N + j) * d;
+            double* dv = dV + (g * N + j) * d;
+            for (long c = 0; c < d; ++c) { dk[c] = 0.0; dv[c] = 0.0; }
+            for (long i = j; i < cu[doc[j] + 1]; ++i) {
+                const double* q = Q + (g * N + i) * d;
+                const double* go = dO + (g * N + i) * d;
+                double gij = dot(go, v, d);
+                double sij = dot(q, k, d);
+                for (long c = 0; c < d; ++c) {
+                    dk[c] += gij * q[c];
+                    dv[c] += sij * go[c];
+                }
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Selected rows of the definition, for sizes where the full double sum is
+ * out of reach.  One group (Q,K,V,dO are [N][d]); rows[r] is a token index.
+ * which: 0 -> O rows, 1 -> dQ rows, 2 -> dK rows, 3 -> dV rows.
+ * For which==0 the dO argument is unused and may be NULL.
+ */
+void lasp2_oracle_def_rows(const double* Q, const double* K, const double* V,
+                           const double* dO, long N, long d,
+                           const long* cu, long n_docs,
+                           const long* rows, long n_rows, int which,
+                           double* out /* [n_rows][d] */)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < n_rows; ++r) {
+        long t = rows[r];
+        double* o = out + r * d;
+        for (long c = 0; c < d; ++c) o[c] = 0.0;
+        if (which == 0) {
+            for (long j = cu[doc[t]]; j <= t; ++j) {
+                double s = dot(Q + t * d, K + j * d, d);
+                for (long c = 0; c < d; ++c) o[c] += s * V[j * d + c];
+            }
+        } else if (which == 1) {
+            for (long j = cu[doc[t]]; j <= t; ++j) {
+                double gij = dot(dO + t * d, V + j * d, d);
+                for (long c = 0; c < d; ++c) o[c] += gij * K[j * d + c];
+            }
+        } else if (which == 2) {
+            for (long i = t; i < cu[doc[t] + 1]; ++i) {
+                double gij = dot(dO + i * d, V + t * d, d);
+                for (long c = 0; c < d; ++c) o[c] += gij * Q[i * d + c];
+            }
+        } else {
+            for (long i = t; i < cu[doc[t] + 1]; ++i) {
+                double sij = dot(Q + i * d, K + t * d, d);
+                for (long c = 0; c < d; ++c) o[c] += sij * dO[i * d + c];
+            }
+        }
+    }
+    free(doc);
+}
+
+/* ------------------------------------------------------------------ */
+/* Recurrent form, Eq. (4).  State update first, then read-out, so the */
+/* diagonal is included; the state is cleared at each document start.  */
+/* ------------------------------------------------------------------ */
+void lasp2_oracle_fwd_rec(const double* Q, const double* K, const double* V,
+                          double* O, long G, long N, long d,
+                          const long* cu, long n_docs)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* M = (double*)malloc(sizeof(double) * (size_t)(d * d));
+        for (long k = 0; k < n_docs; ++k) {
+            memset(M, 0, sizeof(double) * (size_t)(d * d));
+            for (long s = cu[k]; s < cu[k + 1]; ++s) {
+                const double* q = Q + (g * N + s) * d;
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                double* o = O + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] += kk[a] * v[b];
+                for (long b = 0; b < d; ++b) o[b] = 0.0;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) o[b] += q[a] * M[a * d + b];
+            }
+        }
+        free(M);
+    }
+}
+
+/*
+ * Backward of the recurrence.  dq_s = dO_s M_s^T uses the same forward scan;
+ * the adjoint state D_s = sum_{i>=s} q_i^T dO_i runs backwards (update before
+ * use, cleared at each document end):  dk_s = v_s D_s^T,  dv_s = k_s D_s.
+ */
+void lasp2_oracle_bwd_rec(const double* Q, const double* K, const double* V,
+                          const double* dO, double* dQ, double* dK, double* dV,
+                          long G, long N, long d, const long* cu, long n_docs)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* M = (double*)malloc(sizeof(double) * (size_t)(d * d));
+        for (long k = 0; k < n_docs; ++k) {
+            memset(M, 0, sizeof(double) * (size_t)(d * d));
+            for (long s = cu[k]; s < cu[k + 1]; ++s) {
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                const double* go = dO + (g * N + s) * d;
+                double* dq = dQ + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] += kk[a] * v[b];
+                for (long a = 0; a < d; ++a) {
+                    double acc = 0.0;
+                    for (long b = 0; b < d; ++b) acc += go[b] * M[a * d + b];
+                    dq[a] = acc;
+                }
+            }
+            memset(M, 0, sizeof(double) * (size_t)(d * d));
+            for (long s = cu[k + 1] - 1; s >= cu[k]; --s) {
+                const double* q = Q + (g * N + s) * d;
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                const double* go = dO + (g * N + s) * d;
+                double* dk = dK + (g * N + s) * d;
+                double* dv = dV + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] += q[a] * go[b];
+                for (long a = 0; a < d; ++a) {
+                    double acc = 0.0;
+                    for (long b = 0; b < d; ++b) acc += v[b] * M[a * d + b];
+                    dk[a] = acc;
+                }
+                for (long b = 0; b < d; ++b) dv[b] = 0.0;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) dv[b] += kk[a] * M[a * d + b];
+            }
+        }
+        free(M);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* The steps of Algorithm "LASP-2 w/ Masking" over a chunk partition.   */
+/* bounds: n_chunks+1 monotone token offsets (bounds[0]=0, last = N);   */
+/* chunk t holds tokens bounds[t] .. bounds[t+1]-1.                     */
+/* ------------------------------------------------------------------ */
+
+/* line "Compute M_t = K_t^T V_t":  M is [G][n_chunks][d][d] */
+void lasp2_oracle_chunk_states(const double* K, const double* V, double* M,
+                               long G, long N, long d,
+                               const long* bounds, long n_chunks)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            double* m = M + (g * n_chunks + t) * d * d;
+            for (long e = 0; e < d * d; ++e) m[e] = 0.0;
+            for (long s = bounds[t]; s < bounds[t + 1]; ++s) {
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) m[a * d + b] += kk[a] * v[b];
+            }
+        }
+    }
+}
+
+/*
+ * PrefixSum / SuffixSum over the gathered states, exclusive, by the
+ * recursion M_{1:t-1} = M_{1:t-2} + M_{t-1}.
+ *   reverse == 0:  P_t = sum_{s<t} M_s, restarted from zero at every chunk t
+ *                  with first[t] != 0 (chunk t opens a document);
+ *   reverse != 0:  P_t = sum_{s>t} M_s, restarted from zero at every chunk t
+ *                  that closes a document (t == n_chunks-1 or first[t+1]).
+ * first may be NULL (only chunk 0 opens a document).
+ */
+void lasp2_oracle_state_prefix(const double* M, double* P, long G,
+                               long n_chunks, long d, const int* first,
+                               int reverse)
+{
+    long dd = d * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* run = (double*)malloc(sizeof(double) * (size_t)dd);
+        memset(run, 0, sizeof(double) * (size_t)dd);
+        if (!reverse) {
+            for (long t = 0; t < n_chunks; ++t) {
+                if (t == 0 || (first && first[t])) memset(run, 0, sizeof(double) * (size_t)dd);
+                const double* m = M + (g * n_chunks + t) * dd;
+                double* p = P + (g * n_chunks + t) * dd;
+                for (long e = 0; e < dd; ++e) { double add = m[e]; p[e] = run[e]; run[e] += add; }
+            }
+        } else {
+            for (long t = n_chunks - 1; t >= 0; --t) {
+                if (t == n_chunks - 1 || (first && first[t + 1])) memset(run, 0, sizeof(double) * (size_t)dd);
+                const double* m = M + (g * n_chunks + t) * dd;
+                double* p = P + (g * n_chunks + t) * dd;
+                for (long e = 0; e < dd; ++e) { double add = m[e]; p[e] = run[e]; run[e] += add; }
+            }
+        }
+        free(run);
+    }
+}
+
+/*
+ * O_t = [(Q_t K_t^T) (.) Psi] V_t + Q_t M_{1:t-1}: the intra-chunk masked left
+ * product plus the inter-chunk product with the exclusive prefix state P_t.
+ */
+void lasp2_oracle_attn_fwd_chunked(const double* Q, const double* K, const double* V,
+                                   const double* P, double* O,
+                                   long G, long N, long d,
+                                   const long* bounds, long n_chunks)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            long lo = bounds[t], hi = bounds[t + 1], C = hi - lo;
+            if (C <= 0) continue;
+            const double* p = P + (g * n_chunks + t) * d * d;
+            double* S = (double*)malloc(sizeof(double) * (size_t)(C * C));
+            /* S = (Q_t K_t^T) (.) Psi, Psi_ij = 1 if i >= j else 0 */
+            for (long i = 0; i < C; ++i)
+                for (long j = 0; j < C; ++j)
+                    S[i * C + j] = (i >= j)
+                        ? dot(Q + (g * N + lo + i) * d, K + (g * N + lo + j) * d, d) : 0.0;
+            for (long i = 0; i < C; ++i) {
+                double* o = O + (g * N + lo + i) * d;
+                const double* q = Q + (g * N + lo + i) * d;
+                for (long b = 0; b < d; ++b) {
+                    double intra = 0.0, inter = 0.0;
+                    for (long j = 0; j < C; ++j) intra += S[i * C + j] * V[(g * N + lo + j) * d + b];
+                    for (long a = 0; a < d; ++a) inter += q[a] * p[a * d + b];
+                    o[b] = intra + inter;
+                }
+            }
+            free(S);
+        }
+    }
+}
+
+/*
+ * Backward with masking, per chunk t, given the cached prefix P_t = M_{1:t-1}
+ * and the suffix dP_t = dM_{t+1:T}:
+ *   dQ_t = [(dO_t V_t^T)(.)Psi] K_t   + dO_t P_t^T
+ *   dK_t = [(dO_t V_t^T)(.)Psi]^T Q_t + V_t dP_t^T
+ *   dV_t = [(Q_t K_t^T)(.)Psi]^T dO_t + K_t dP_t
+ */
+void lasp2_oracle_attn_bwd_chunked(const double* Q, const double* K, const double* V,
+                                   const double* dO, const double* P, const double* dP,
+                                   double* dQ, double* dK, double* dV,
+                                   long G, long N, long d,
+                                   const long* bounds, long n_chunks)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            long lo = bounds[t], hi = bounds[t + 1], C = hi - lo;
+            if (C <= 0) continue;
+            const double* p = P + (g * n_chunks + t) * d * d;
+            const double* dp = dP + (g * n_chunks + t) * d * d;
+            double* S = (double*)malloc(sizeof(double) * (size_t)(C * C));
+            double* Gm = (double*)malloc(sizeof(double) * (size_t)(C * C));
+            for (long i = 0; i < C; ++i)
+                for (long j = 0; j < C; ++j) {
+                    int keep = (i >= j);
+                    S[i * C + j] = keep ? dot(Q + (g * N + lo + i) * d, K + (g * N + lo + j) * d, d) : 0.0;
+                    Gm[i * C + j] = keep ? dot(dO + (g * N + lo + i) * d, V + (g * N + lo + j) * d, d) : 0.0;
+                }
+            for (long i = 0; i < C; ++i) {
+                const double* go = dO + (g * N + lo + i) * d;
+                double* dq = dQ + (g * N + lo + i) * d;
+                for (long a = 0; a < d; ++a) {
+                    double intra = 0.0, inter = 0.0;
+                    for (long j = 0; j < C; ++j) intra += Gm[i * C + j] * K[(g * N + lo + j) * d + a];
+                    for (long b = 0; b < d; ++b) inter += go[b] * p[a * d + b];
+                    dq[a] = intra + inter;
+                }
+            }
+            for (long j = 0; j < C; ++j) {
+                const double* kk = K + (g * N + lo + j) * d;
+                const double* v = V + (g * N + lo + j) * d;
+                double* dk = dK + (g * N + lo + j) * d;
+                double* dv = dV + (g * N + lo + j) * d;
+                for (long a = 0; a < d; ++a) {
+                    double intra = 0.0, inter = 0.0;
+                    for (long i = 0; i < C; ++i) intra += Gm[i * C + j] * Q[(g * N + lo + i) * d + a];
+                    for (long b = 0; b < d; ++b) inter += v[b] * dp[a * d + b];
+                    dk[a] = intra + inter;
+                }
+                for (long b = 0; b < d; ++b) {
+                    double intra = 0.0, inter = 0.0;
+                    for (long i = 0; i < C; ++i) intra += S[i * C + j] * dO[(g * N + lo + i) * d + b];
+                    for (long a = 0; a < d; ++a) inter += kk[a] * dp[a * d + b];
+                    dv[b] = intra + inter;
+                }
+            }
+            free(S);
+            free(Gm);
+        }
+    }
+}
