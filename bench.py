@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Throughput of the LASP-2 hot path on one MI355X: one "step" is a full forward
+(chunk_states -> state_prefix -> attn_fwd) plus a full backward (attn_bwd: dM states,
+suffix combine, dQ/dK/dV) of one attention layer over one batch of synthetic input
+that is already resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+
+Prints ONE JSON line.  `value` is tokens/s for the layer; `roofline` prices the
+dominant kernel (the fused attention pass) against HBM peak using its algorithmic
+bytes and its HIP-event duration measured inside the timed loop; `cpu_baseline`
+is the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def nominal_flops_per_token_head(d, C):
+    """Algorithmic flop count of the method: 7 masked/unmasked C x C products counted on the
+    causal triangle plus 6 state products (forward 2, backward 4) of 2 d^2 each."""
+    return 7 * d * (C + 1) + 12 * d * d
+
+
+def cpu_baseline(cfg, sample_tokens):
+    """The oracle (recurrent form, fp64) on all H heads of a `sample_tokens`-long prefix."""
+    import numpy as np
+    import oracle
+    from paper_2502_07563_amd import synth
+    G = cfg["B"] * cfg["H"]
+    G = min(G, cfg["H"])          # one batch row is enough for a per-layer rate
+    x = {n: synth.gen_tensor(cfg["seed"], n, G, sample_tokens, cfg["d"], cfg["dtype"]).astype(np.float64)
+         for n in ("Q", "K", "V", "dO")}
+    t0 = time.perf_counter()
+    oracle.fwd_rec(x["Q"], x["K"], x["V"])
+    oracle.bwd_rec(x["Q"], x["K"], x["V"], x["dO"])
+    dt = time.perf_counter() - t0
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"recurrent fp64 oracle, fwd+bwd, {G} heads x first {sample_tokens} tokens "
+                      f"of the workload, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (outside the timed region) so a "
+                         "counter run contains a kernel of known traffic")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    from paper_2502_07563_amd import synth
+
+    cfg = synth.CONFIGS[args.workload]
+    B, H, N, d, C, L = (cfg[k] for k in ("B", "H", "N", "d", "C", "L"))
+    dtype = cfg["dtype"]
+    cu = synth.config_offsets(cfg)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu)
+    tdt = p.torch_dtype
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg["seed"])
+    mk = lambda: (torch.randn((B, H, N, d), generator=gen, device=dev, dtype=torch.float32)
+                  / math.sqrt(d)).to(tdt)
+    Q, K, V, dO = mk(), mk(), mk(), mk()
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    P = bd.alloc_states(p)
+    ws = bd.alloc_states(p)
+    T_s = P.shape[2]
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        if record:
+            e = [ev() for _ in range(5)]
+            e[0].record()
+        bd.lasp2_chunk_states(p, K, V, P)
+        if record:
+            e[1].record()
+        bd.lasp2_state_prefix(p, P, P, False)
+        if record:
+            e[2].record()
+        bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+        if record:
+            e[3].record()
+        bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
+        if record:
+            e[4].record()
+            marks.append(e)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt * 1e3 / args.steps
+    tokens = B * N
+    value = tokens / (dt / args.steps)
+    seg = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]
+
+    esz = 2 if dtype == "bf16" else 4
+    # fused attention pass, one launch: reads A, Bk, Cv and the slot states, writes out
+    attn_bytes = 4 * B * H * N * d * esz + B * H * T_s * d * d * 4
+    attn_ms = seg[2]
+    achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+    flops_nominal = nominal_flops_per_token_head(d, C) * tokens * H
+    out = {
+        "metric": "fwd+bwd tokens/s per layer",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={B} H={H} N={N} d={d} C={C} L={L or C}"
+                               + (f" packed {cfg['n_docs']} docs" if cu is not None else ""),
+                   "state_slots": int(T_s)},
+        "ms": {"chunk_states": seg[0], "state_prefix": seg[1], "attn_fwd": seg[2], "attn_bwd": seg[3]},
+        "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
+        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel (as launched by lasp2_attn_fwd)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,148 @@
+/*
+ * lasp2.h - C ABI of the single-GPU hot path of LASP-2 with masking:
+ * chunked causal (unnormalised, identity-kernel) linear attention, forward and
+ * backward, for AMD MI355X (gfx950).
+ *
+ * Problem statement (LASP-2 paper, Sec. "Preliminary", Eq. (3); Sec. "LASP-2
+ * with Masking", Algorithm "LASP-2 w/ Masking"; appendix Algorithm "LASP-2 w/
+ * Masking (Backward Pass)"): per (batch, head), Q, K, V in R^{N x d};
+ *     o_s = sum_{i<=s} (q_s . k_i) v_i .
+ * The sequence is cut into chunks; chunk t contributes a d x d memory state
+ * M_t = K_t^T V_t.  The paper all-gathers the states of all devices; here all
+ * of them sit in one HBM array [B,H,T_s,d,d] and an exclusive prefix combine
+ * gives M_{1:t-1}.  The output of chunk t is
+ *     O_t = [(Q_t K_t^T) (.) Psi] V_t + Q_t M_{1:t-1},   Psi_ij = [i >= j],
+ * and the backward mirrors it with dM_t = Q_t^T dO_t and the reverse
+ * (suffix) combine dM_{t+1:T}.
+ *
+ * Two granularities (the result depends on neither):
+ *   C  chunk length: the side of the masked quadratic block and the period at
+ *      which the inter-chunk state operand is refreshed inside a kernel;
+ *   L  tokens per state slot, a multiple of C (0 means L = C, the paper-literal
+ *      layout with one state per chunk).  One slot is what one sequence-
+ *      parallel rank would own; its chunks are walked by one workgroup that
+ *      carries the running state on chip.
+ *
+ * Slots.  Unpacked input: every (b,h) row of N tokens has T_s = ceil(N/L)
+ * slots, slot s = tokens [s*L, min(N,(s+1)*L)).  Packed input (B must be 1):
+ * document k = tokens [cu[k], cu[k+1]) has ceil(len_k/L) slots of its own,
+ * slots never span documents, and T_s is their total, in document order.
+ * No state crosses a document boundary (paper appendix "Variable Length",
+ * read as a block-diagonal causal mask).  Ragged last chunks/slots are fine.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers, 16-byte aligned, contiguous,
+ *     d fastest: Q,K,V,O,dO,dQ,dK,dV are [B,H,N,d] in `dtype` (fp32 or bf16);
+ *     states M,P and the workspace are fp32, [B,H,T_s,d,d] with M[a][b] =
+ *     sum_tokens k[a]*v[b].
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls and is re-entrant.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work; outputs are valid once the stream has been
+ *     synchronised.  The descriptor and `cu_seqlens_host` are read during the
+ *     call and need not outlive it; `cu_seqlens_dev` is read by the kernels
+ *     and must stay valid until they have run.
+ *   - Return value: LASP2_OK or a negative lasp2_status_t.  Argument errors
+ *     are detected on the host before anything is launched and never touch
+ *     the device.  Nothing aborts or throws.
+ *   - B, H or N equal to 0 is a valid empty problem: the call returns LASP2_OK
+ *     and launches nothing (pointers are then not examined).
+ *   - Supported: d in {16, 32, 64, 128}; 1 <= C <= 512.  The MFMA kernels
+ *     cover bf16, d = 128, C in {64, 128, 256}; any other supported
+ *     combination runs the plain fp32-FMA kernels.  There is no CPU fallback.
+ */
+#ifndef LASP2_H
+#define LASP2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LASP2_OK = 0,
+    LASP2_ERR_NULL = -1,        /* a required pointer is NULL                           */
+    LASP2_ERR_SHAPE = -2,       /* B,H,N < 0; d or C outside the supported set; L not a
+                                   positive multiple of C; sizes overflow int64         */
+    LASP2_ERR_DTYPE = -3,       /* dtype is neither LASP2_F32 nor LASP2_BF16            */
+    LASP2_ERR_SEQLENS = -4,     /* packed: B != 1, cu[0] != 0, cu[n] != N, not strictly
+                                   increasing, or only one of the two cu pointers given */
+    LASP2_ERR_WORKSPACE = -5,   /* workspace smaller than lasp2_workspace_size()        */
+    LASP2_ERR_ALIGN = -6,       /* a device pointer is not 16-byte aligned              */
+    LASP2_ERR_LAUNCH = -7       /* the HIP runtime reported an error at launch          */
+} lasp2_status_t;
+
+typedef enum { LASP2_F32 = 0, LASP2_BF16 = 1 } lasp2_dtype_t;
+
+typedef struct lasp2_desc {
+    int32_t B, H, N, d;              /* tensor shape [B,H,N,d]                                   */
+    int32_t C;                       /* chunk length                                             */
+    int32_t L;                       /* tokens per state slot; 0 => C; else a multiple of C      */
+    int32_t dtype;                   /* lasp2_dtype_t of the eight [B,H,N,d] tensors             */
+    int32_t n_seqs;                  /* packed: number of documents (>= 1); 0 => not packed      */
+    const int32_t* cu_seqlens_host;  /* HOST  ptr, n_seqs+1 offsets, cu[0]=0 < ... < cu[n]=N     */
+    const int32_t* cu_seqlens_dev;   /* DEVICE ptr holding the same n_seqs+1 values              */
+} lasp2_desc_t;
+
+/* Number of state slots T_s per (b,h) for this descriptor (see "Slots" above). */
+int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s);
+
+/* Bytes of device scratch lasp2_attn_bwd needs: one fp32 state array
+ * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine. */
+int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
+
+/*
+ * Chunk states, Algorithm "LASP-2 w/ Masking" line "Compute M_t = K_t^T V_t",
+ * one state per slot: M[b,h,s] = sum over the slot's tokens of k^T v (fp32).
+ * With (Q, dO) in place of (K, V) it yields dM_t = Q_t^T dO_t of the backward.
+ * In:  K, V [B,H,N,d] (device, `dtype`).   Out: M [B,H,T_s,d,d] fp32 (device).
+ */
+int lasp2_chunk_states(const lasp2_desc_t* desc, const void* K, const void* V,
+                       float* M, void* stream);
+
+/*
+ * Prefix combine that stands in for AllGather + PrefixSum (forward) and
+ * AllGather + SuffixSum (backward): exclusive, restarted at document edges.
+ *   reverse == 0:  P[s] = sum_{r<s, same doc} M[r]   (M_{1:t-1};  first = 0)
+ *   reverse != 0:  P[s] = sum_{r>s, same doc} M[r]   (dM_{t+1:T}; last  = 0)
+ * In: M [B,H,T_s,d,d] fp32.  Out: P same shape; P may alias M exactly
+ * (in place); partial overlap is not allowed.
+ */
+int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P,
+                       int reverse, void* stream);
+
+/*
+ * Fused forward, Algorithm "LASP-2 w/ Masking" lines O_intra, O_inter, O_t:
+ * for every chunk t of every slot, O_t = [(Q_t K_t^T)(.)Psi] V_t + Q_t M_{1:t-1},
+ * where M_{1:t-1} = P[slot] + the states of the slot's earlier chunks (carried
+ * on chip).  In: Q,K,V [B,H,N,d]; P [B,H,T_s,d,d] fp32 from lasp2_state_prefix
+ * (reverse = 0).  Out: O [B,H,N,d] in `dtype`, written once.
+ */
+int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
+                   const void* V, const float* P, void* O, void* stream);
+
+/*
+ * Backward, Algorithm "LASP-2 w/ Masking (Backward Pass)":
+ *   dM_t = Q_t^T dO_t, suffix combine dM_{t+1:T} (both into `workspace`), then
+ *   dQ_t = [(dO_t V_t^T)(.)Psi] K_t   + dO_t M_{1:t-1}^T
+ *   dK_t = [(dO_t V_t^T)(.)Psi]^T Q_t + V_t dM_{t+1:T}^T
+ *   dV_t = [(Q_t K_t^T)(.)Psi]^T dO_t + K_t dM_{t+1:T}
+ * In: Q,K,V,dO [B,H,N,d]; P = the forward's cached prefix array (the paper
+ * keeps M_{1:t-1} in HBM for this purpose).  Out: dQ,dK,dV [B,H,N,d].
+ * `workspace`: device scratch of at least lasp2_workspace_size() bytes,
+ * 16-byte aligned; contents on return are the suffix states dM_{t+1:T}.
+ */
+int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
+                   const void* V, const void* dO, const float* P,
+                   void* dQ, void* dK, void* dV,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* lasp2_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASP2_H */

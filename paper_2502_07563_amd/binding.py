@@ -1,0 +1,161 @@
+"""ctypes binding of liblasp2.so: same names as the C ABI in include/lasp2.h.
+
+Argument marshalling only.  Tensors are torch CUDA tensors (torch is used for
+device memory and streams); every step of the computation runs in the HIP
+library.  There is no fallback: if the library is missing, importing the
+entry points raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liblasp2.so")
+
+LASP2_F32, LASP2_BF16 = 0, 1
+STATUS = {0: "LASP2_OK", -1: "LASP2_ERR_NULL", -2: "LASP2_ERR_SHAPE", -3: "LASP2_ERR_DTYPE",
+          -4: "LASP2_ERR_SEQLENS", -5: "LASP2_ERR_WORKSPACE", -6: "LASP2_ERR_ALIGN",
+          -7: "LASP2_ERR_LAUNCH"}
+
+
+class Desc(ctypes.Structure):
+    """Mirror of lasp2_desc_t."""
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("C", ctypes.c_int32), ("L", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
+                ("cu_seqlens_host", ctypes.c_void_p), ("cu_seqlens_dev", ctypes.c_void_p)]
+
+
+class Lasp2Error(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {STATUS.get(code, code)} ({status_string(code)})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2502_07563_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64p, szp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)
+        dp = ctypes.POINTER(Desc)
+        L.lasp2_num_slots.argtypes = [dp, i64p]
+        L.lasp2_workspace_size.argtypes = [dp, szp]
+        L.lasp2_chunk_states.argtypes = [dp, vp, vp, vp, vp]
+        L.lasp2_state_prefix.argtypes = [dp, vp, vp, ctypes.c_int, vp]
+        L.lasp2_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.lasp2_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.lasp2_status_string.argtypes = [ctypes.c_int]
+        L.lasp2_status_string.restype = ctypes.c_char_p
+        for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
+                     "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().lasp2_status_string(int(code)).decode()
+
+
+class Problem:
+    """A descriptor plus the host/device copies of the packed-sequence offsets it points to."""
+
+    def __init__(self, B, H, N, d, C, L=0, dtype="bf16", cu_seqlens=None, device="cuda"):
+        self.B, self.H, self.N, self.d, self.C, self.L = B, H, N, d, C, L
+        self.dtype = dtype
+        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+        self.desc = Desc(B=B, H=H, N=N, d=d, C=C, L=L,
+                         dtype={"f32": LASP2_F32, "bf16": LASP2_BF16}[dtype], n_seqs=0,
+                         cu_seqlens_host=None, cu_seqlens_dev=None)
+        self._cu_host = self._cu_dev = None
+        if cu_seqlens is not None:
+            self._cu_host = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+            self._cu_dev = torch.from_numpy(self._cu_host).to(device)
+            self.desc.n_seqs = len(self._cu_host) - 1
+            self.desc.cu_seqlens_host = self._cu_host.ctypes.data
+            self.desc.cu_seqlens_dev = self._cu_dev.data_ptr()
+
+    @property
+    def ref(self):
+        return ctypes.byref(self.desc)
+
+
+def _check(code, where):
+    if code != 0:
+        raise Lasp2Error(code, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def lasp2_num_slots(p: Problem) -> int:
+    out = ctypes.c_int64(0)
+    _check(lib().lasp2_num_slots(p.ref, ctypes.byref(out)), "lasp2_num_slots")
+    return out.value
+
+
+def lasp2_workspace_size(p: Problem) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lasp2_workspace_size(p.ref, ctypes.byref(out)), "lasp2_workspace_size")
+    return out.value
+
+
+def lasp2_chunk_states(p: Problem, K, V, M, stream=None):
+    _check(lib().lasp2_chunk_states(p.ref, _ptr(K), _ptr(V), _ptr(M), _stream(stream)),
+           "lasp2_chunk_states")
+
+
+def lasp2_state_prefix(p: Problem, M, P, reverse=False, stream=None):
+    _check(lib().lasp2_state_prefix(p.ref, _ptr(M), _ptr(P), 1 if reverse else 0, _stream(stream)),
+           "lasp2_state_prefix")
+
+
+def lasp2_attn_fwd(p: Problem, Q, K, V, P, O, stream=None):
+    _check(lib().lasp2_attn_fwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(P), _ptr(O), _stream(stream)),
+           "lasp2_attn_fwd")
+
+
+def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lasp2_attn_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(P), _ptr(dQ),
+                                _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
+                                _stream(stream)), "lasp2_attn_bwd")
+
+
+def alloc_states(p: Problem, device="cuda"):
+    """fp32 [B,H,T_s,d,d] state array (device memory from torch)."""
+    return torch.empty((p.B, p.H, lasp2_num_slots(p), p.d, p.d), dtype=torch.float32, device=device)
+
+
+def forward(p: Problem, Q, K, V, stream=None):
+    """chunk_states -> state_prefix (in place) -> attn_fwd.  Returns (O, P)."""
+    P = alloc_states(p, Q.device)
+    O = torch.empty_like(Q)
+    lasp2_chunk_states(p, K, V, P, stream)
+    lasp2_state_prefix(p, P, P, False, stream)
+    lasp2_attn_fwd(p, Q, K, V, P, O, stream)
+    return O, P
+
+
+def backward(p: Problem, Q, K, V, dO, P, stream=None):
+    """attn_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, dP)."""
+    ws = alloc_states(p, Q.device)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws, stream)
+    return dQ, dK, dV, ws

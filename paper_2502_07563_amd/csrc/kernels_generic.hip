@@ -1,0 +1,273 @@
+// Plain fp32-FMA kernels of liblasp2: every supported (dtype, d, C) runs here
+// unless the bf16 MFMA kernels take it.  They favour being easy to check over
+// speed: one workgroup per state slot, fp32 arithmetic throughout, fixed
+// summation order (run-to-run bit-identical, no atomics).
+//
+// Also holds the state prefix/suffix kernel, which is the same for every path.
+#include "lasp2_common.h"
+
+#include <hip/hip_bf16.h>
+
+namespace lasp2 {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRows = 16;  // query rows handled per pass of the attention kernel
+
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const __hip_bfloat16* p) { return __bfloat162float(*p); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(__hip_bfloat16* p, float v) { *p = __float2bfloat16(v); }
+
+// M[slot] = sum over the slot's tokens of k^T v.  Thread (ty,tx) of a 16x16 grid owns
+// the elements (ty + 16 i, tx + 16 j).
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void states_generic_kernel(Geom g, const T* __restrict__ K,
+                                                                  const T* __restrict__ V,
+                                                                  float* __restrict__ M)
+{
+    constexpr int TM = D / 16;
+    const int s = blockIdx.x, grp = blockIdx.y;
+    const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+
+    float acc[TM][TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) acc[i][j] = 0.f;
+
+    for (int t = 0; t < len; ++t) {
+        const T* kr = K + gbase + (size_t)(tok0 + t) * D;
+        const T* vr = V + gbase + (size_t)(tok0 + t) * D;
+        float kk[TM], vv[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) kk[i] = ld(kr + ty + 16 * i);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) vv[j] = ld(vr + tx + 16 * j);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) acc[i][j] = fmaf(kk[i], vv[j], acc[i][j]);
+    }
+    float* m = M + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) m[(ty + 16 * i) * D + tx + 16 * j] = acc[i][j];
+}
+
+// One workgroup walks the chunks of one slot.  Shared memory: the running state
+// (D x D fp32), one block of kRows rows of A, and their masked scores.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void attn_generic_kernel(
+    Geom g, const T* __restrict__ A, const T* __restrict__ Bk, const T* __restrict__ Cv,
+    const float* __restrict__ state, T* __restrict__ out, int transpose_state, int reverse)
+{
+    constexpr int TM = D / 16;
+    constexpr int AS = D + 1;  // padded row stride of the A block
+    extern __shared__ float smem[];
+    float* Mst = smem;                 // D*D
+    float* Ablk = Mst + D * D;         // kRows*AS
+    float* S = Ablk + kRows * AS;      // kRows*(C+1)
+    const int SS = g.C + 1;
+
+    const int tid = threadIdx.x;
+    const int s = blockIdx.x, grp = blockIdx.y;
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+    const float* st0 = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+
+    for (int e = tid; e < D * D; e += kThreads) {
+        int a = e / D, b = e % D;
+        Mst[e] = transpose_state ? st0[b * D + a] : st0[e];
+    }
+    __syncthreads();
+
+    const int nch = (len + g.C - 1) / g.C;
+    for (int ci = 0; ci < nch; ++ci) {
+        const int c = reverse ? nch - 1 - ci : ci;
+        const int c0 = tok0 + c * g.C;
+        const int clen = min(g.C, tok0 + len - c0);
+
+        for (int r0 = 0; r0 < clen; r0 += kRows) {
+            const int rl = min(kRows, clen - r0);
+            for (int idx = tid; idx < kRows * D; idx += kThreads) {
+                int r = idx / D, a = idx % D;
+                Ablk[r * AS + a] = (r < rl) ? ld(A + gbase + (size_t)(c0 + r0 + r) * D + a) : 0.f;
+            }
+            __syncthreads();
+            // masked scores S[r][j] = a_{r0+r} . b_j on allowed pairs, else 0
+            for (int idx = tid; idx < kRows * clen; idx += kThreads) {
+                int r = idx % kRows, j = idx / kRows;
+                int i = r0 + r;
+                bool keep = (r < rl) && (reverse ? (j >= i) : (j <= i));
+                float acc = 0.f;
+                if (keep) {
+                    const T* br = Bk + gbase + (size_t)(c0 + j) * D;
+                    for (int a = 0; a < D; ++a) acc = fmaf(Ablk[r * AS + a], ld(br + a), acc);
+                }
+                S[r * SS + j] = acc;
+            }
+            __syncthreads();
+            // out[r][b] = sum_j S[r][j] c_j[b] + sum_a A[r][a] Mst[a][b]
+            for (int idx = tid; idx < kRows * D; idx += kThreads) {
+                int r = idx / D, b = idx % D;
+                if (r >= rl) continue;
+                int i = r0 + r;
+                int jlo = reverse ? i : 0, jhi = reverse ? clen - 1 : i;
+                float intra = 0.f, inter = 0.f;
+                for (int j = jlo; j <= jhi; ++j)
+                    intra = fmaf(S[r * SS + j], ld(Cv + gbase + (size_t)(c0 + j) * D + b), intra);
+                for (int a = 0; a < D; ++a) inter = fmaf(Ablk[r * AS + a], Mst[a * D + b], inter);
+                st(out + gbase + (size_t)(c0 + i) * D + b, intra + inter);
+            }
+            __syncthreads();
+        }
+
+        if (ci + 1 < nch) {
+            // running state += Bk_c^T Cv_c ; each thread owns its own elements
+            const int ty = tid / 16, tx = tid % 16;
+            float acc[TM][TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) acc[i][j] = 0.f;
+            for (int t = 0; t < clen; ++t) {
+                const T* br = Bk + gbase + (size_t)(c0 + t) * D;
+                const T* cr = Cv + gbase + (size_t)(c0 + t) * D;
+                float bb[TM], cc[TM];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) bb[i] = ld(br + ty + 16 * i);
+#pragma unroll
+                for (int j = 0; j < TM; ++j) cc[j] = ld(cr + tx + 16 * j);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) acc[i][j] = fmaf(bb[i], cc[j], acc[i][j]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) Mst[(ty + 16 * i) * D + tx + 16 * j] += acc[i][j];
+            __syncthreads();
+        }
+    }
+}
+
+// Exclusive prefix (or suffix) over the slots of each group, restarted per document.
+// One thread owns four adjacent state elements and walks the slots in order; loads are
+// batched ahead of the stores so that in-place use (P == M) stays correct and the
+// memory system sees several requests in flight.
+constexpr int kScanBatch = 8;
+
+__global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const float* M, float* P,
+                                                                int reverse)
+{
+    const int dd = g.d * g.d;
+    const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (e >= dd) return;
+    const size_t base = (size_t)blockIdx.y * (size_t)g.T_s * dd + e;
+    const int ndocs = g.n_seqs ? g.n_seqs : 1;
+    const int step = reverse ? -1 : 1;
+    int s = reverse ? g.T_s - 1 : 0;
+    for (int kk = 0; kk < ndocs; ++kk) {
+        const int k = reverse ? ndocs - 1 - kk : kk;
+        const int dlen = g.n_seqs ? (g.cu[k + 1] - g.cu[k]) : g.N;
+        const int ns = (int)(((int64_t)dlen + g.L - 1) / g.L);
+        float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int r = 0; r < ns; r += kScanBatch) {
+            float4 m[kScanBatch];
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u)
+                if (r + u < ns)
+                    m[u] = *reinterpret_cast<const float4*>(M + base + (size_t)(s + step * u) * dd);
+#pragma unroll
+            for (int u = 0; u < kScanBatch; ++u)
+                if (r + u < ns) {
+                    *reinterpret_cast<float4*>(P + base + (size_t)(s + step * u) * dd) = run;
+                    run.x += m[u].x; run.y += m[u].y; run.z += m[u].z; run.w += m[u].w;
+                }
+            s += step * min(kScanBatch, ns - r);
+        }
+    }
+}
+
+template <typename T>
+hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, hipStream_t st)
+{
+    dim3 grid(g.T_s, g.G), block(kThreads);
+    switch (g.d) {
+        case 16: hipLaunchKernelGGL((states_generic_kernel<T, 16>), grid, block, 0, st, g, K, V, M); break;
+        case 32: hipLaunchKernelGGL((states_generic_kernel<T, 32>), grid, block, 0, st, g, K, V, M); break;
+        case 64: hipLaunchKernelGGL((states_generic_kernel<T, 64>), grid, block, 0, st, g, K, V, M); break;
+        default: hipLaunchKernelGGL((states_generic_kernel<T, 128>), grid, block, 0, st, g, K, V, M); break;
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t attn_generic_TD(const Geom& g, const T* A, const T* Bk, const T* Cv, const float* state,
+                           T* out, int tr, int rev, hipStream_t st)
+{
+    size_t smem = sizeof(float) * ((size_t)D * D + (size_t)kRows * (D + 1) + (size_t)kRows * (g.C + 1));
+    auto kern = attn_generic_kernel<T, D>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(g.T_s, g.G), block(kThreads);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, A, Bk, Cv, state, out, tr, rev);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t attn_generic_T(const Geom& g, const T* A, const T* Bk, const T* Cv, const float* state,
+                          T* out, int tr, int rev, hipStream_t st)
+{
+    switch (g.d) {
+        case 16: return attn_generic_TD<T, 16>(g, A, Bk, Cv, state, out, tr, rev, st);
+        case 32: return attn_generic_TD<T, 32>(g, A, Bk, Cv, state, out, tr, rev, st);
+        case 64: return attn_generic_TD<T, 64>(g, A, Bk, Cv, state, out, tr, rev, st);
+        default: return attn_generic_TD<T, 128>(g, A, Bk, Cv, state, out, tr, rev, st);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_states_generic(const Geom& g, int dtype, const void* K, const void* V, float* M,
+                                 hipStream_t st)
+{
+    if (dtype == LASP2_F32)
+        return states_generic_T(g, static_cast<const float*>(K), static_cast<const float*>(V), M, st);
+    return states_generic_T(g, static_cast<const __hip_bfloat16*>(K),
+                            static_cast<const __hip_bfloat16*>(V), M, st);
+}
+
+hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const void* Bk,
+                               const void* Cv, const float* state, void* out, int transpose_state,
+                               int reverse, hipStream_t st)
+{
+    if (dtype == LASP2_F32)
+        return attn_generic_T(g, static_cast<const float*>(A), static_cast<const float*>(Bk),
+                              static_cast<const float*>(Cv), state, static_cast<float*>(out),
+                              transpose_state, reverse, st);
+    return attn_generic_T(g, static_cast<const __hip_bfloat16*>(A),
+                          static_cast<const __hip_bfloat16*>(Bk),
+                          static_cast<const __hip_bfloat16*>(Cv), state,
+                          static_cast<__hip_bfloat16*>(out), transpose_state, reverse, st);
+}
+
+hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, hipStream_t st)
+{
+    const int dd = g.d * g.d;
+    dim3 grid((dd / 4 + kThreads - 1) / kThreads, g.G), block(kThreads);
+    hipLaunchKernelGGL(state_prefix_kernel, grid, block, 0, st, g, M, P, reverse);
+    return hipGetLastError();
+}
+
+}  // namespace lasp2

@@ -1,0 +1,207 @@
+// Host side of liblasp2: argument validation, slot arithmetic and kernel dispatch
+// for the entry points declared in include/lasp2.h.  Every argument error is
+// reported before the first HIP call, so the error paths run on a machine
+// without a GPU.
+#include "lasp2_common.h"
+
+#include <limits.h>
+
+namespace lasp2 {
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool supported_d(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+
+// Validates the descriptor and fills the kernel geometry.  *empty is set when
+// there is nothing to compute.
+int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
+{
+    if (!desc) return LASP2_ERR_NULL;
+    if (desc->dtype != LASP2_F32 && desc->dtype != LASP2_BF16) return LASP2_ERR_DTYPE;
+    if (desc->B < 0 || desc->H < 0 || desc->N < 0) return LASP2_ERR_SHAPE;
+    if (!supported_d(desc->d)) return LASP2_ERR_SHAPE;
+    if (desc->C < 1 || desc->C > 512) return LASP2_ERR_SHAPE;
+    if (desc->L < 0) return LASP2_ERR_SHAPE;
+    int64_t L = desc->L == 0 ? desc->C : desc->L;
+    if (L % desc->C != 0) return LASP2_ERR_SHAPE;
+    int64_t G = (int64_t)desc->B * desc->H;
+    if (G > 65535) return LASP2_ERR_SHAPE;  // grid.y carries the group index
+    // every element offset must fit int64 with a wide margin
+    if (G > 0 && (int64_t)desc->N > (INT64_MAX / 8) / (G * desc->d)) return LASP2_ERR_SHAPE;
+    if (desc->n_seqs < 0) return LASP2_ERR_SEQLENS;
+
+    int64_t T_s = 0;
+    if (desc->n_seqs > 0) {
+        if (!desc->cu_seqlens_host || !desc->cu_seqlens_dev) return LASP2_ERR_SEQLENS;
+        if (desc->B != 1) return LASP2_ERR_SEQLENS;
+        const int32_t* cu = desc->cu_seqlens_host;
+        if (cu[0] != 0 || cu[desc->n_seqs] != desc->N) return LASP2_ERR_SEQLENS;
+        for (int k = 0; k < desc->n_seqs; ++k) {
+            if (cu[k + 1] <= cu[k]) return LASP2_ERR_SEQLENS;
+            T_s += ((int64_t)(cu[k + 1] - cu[k]) + L - 1) / L;
+        }
+        if (reinterpret_cast<uintptr_t>(desc->cu_seqlens_dev) & 3u) return LASP2_ERR_ALIGN;
+    } else {
+        if (desc->cu_seqlens_host || desc->cu_seqlens_dev) return LASP2_ERR_SEQLENS;
+        T_s = ((int64_t)desc->N + L - 1) / L;
+    }
+    if (T_s > INT32_MAX) return LASP2_ERR_SHAPE;
+    if (G > 0 && T_s > (INT64_MAX / 8) / (G * desc->d * desc->d)) return LASP2_ERR_SHAPE;
+
+    g->G = (int32_t)G;
+    g->N = desc->N;
+    g->d = desc->d;
+    g->C = desc->C;
+    g->L = L;
+    g->T_s = (int32_t)T_s;
+    g->n_seqs = desc->n_seqs;
+    g->cu = desc->cu_seqlens_dev;
+    *empty = (G == 0 || desc->N == 0);
+    return LASP2_OK;
+}
+
+int check_ptrs(std::initializer_list<const void*> ptrs)
+{
+    for (const void* p : ptrs)
+        if (!p) return LASP2_ERR_NULL;
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return LASP2_ERR_ALIGN;
+    return LASP2_OK;
+}
+
+int from_hip(hipError_t e) { return e == hipSuccess ? LASP2_OK : LASP2_ERR_LAUNCH; }
+
+hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, float* M,
+                      hipStream_t st)
+{
+    if (mfma_path_supported(g, dtype)) return launch_states_mfma(g, K, V, M, st);
+    return launch_states_generic(g, dtype, K, V, M, st);
+}
+
+hipError_t run_attn(const Geom& g, int dtype, const void* A, const void* Bk, const void* Cv,
+                    const float* state, void* out, int transpose_state, int reverse,
+                    hipStream_t st)
+{
+    if (mfma_path_supported(g, dtype))
+        return launch_attn_mfma(g, A, Bk, Cv, state, out, transpose_state, reverse, st);
+    return launch_attn_generic(g, dtype, A, Bk, Cv, state, out, transpose_state, reverse, st);
+}
+
+}  // namespace
+}  // namespace lasp2
+
+using namespace lasp2;
+
+extern "C" {
+
+int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s)
+{
+    if (!T_s) return LASP2_ERR_NULL;
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    *T_s = g.T_s;
+    return LASP2_OK;
+}
+
+int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
+{
+    if (!bytes) return LASP2_ERR_NULL;
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    *bytes = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    return LASP2_OK;
+}
+
+int lasp2_chunk_states(const lasp2_desc_t* desc, const void* K, const void* V, float* M,
+                       void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({K, V, M});
+    if (rc != LASP2_OK) return rc;
+    return from_hip(run_states(g, desc->dtype, K, V, M, (hipStream_t)stream));
+}
+
+int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P, int reverse,
+                       void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({M, P});
+    if (rc != LASP2_OK) return rc;
+    return from_hip(launch_state_prefix(g, M, P, reverse ? 1 : 0, (hipStream_t)stream));
+}
+
+int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                   const float* P, void* O, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, K, V, P, O});
+    if (rc != LASP2_OK) return rc;
+    return from_hip(run_attn(g, desc->dtype, Q, K, V, P, O, 0, 0, (hipStream_t)stream));
+}
+
+int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                   const void* dO, const float* P, void* dQ, void* dK, void* dV,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, K, V, dO, P, dQ, dK, dV, workspace});
+    if (rc != LASP2_OK) return rc;
+    size_t need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    if (workspace_bytes < need) return LASP2_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    float* dP = static_cast<float*>(workspace);
+    // dM_t = Q_t^T dO_t per slot, then its suffix combine in place.
+    hipError_t e = run_states(g, desc->dtype, Q, dO, dP, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    e = launch_state_prefix(g, dP, dP, 1, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
+    // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
+    e = run_attn(g, desc->dtype, dO, V, K, P, dQ, 1, 0, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    // dV: anti-causal problem with (K, Q, dO); state dM_{t+1:T} = sum Q^T dO.
+    e = run_attn(g, desc->dtype, K, Q, dO, dP, dV, 0, 1, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
+    e = run_attn(g, desc->dtype, V, dO, Q, dP, dK, 1, 1, st);
+    return from_hip(e);
+}
+
+const char* lasp2_status_string(int status)
+{
+    switch (status) {
+        case LASP2_OK: return "ok";
+        case LASP2_ERR_NULL: return "a required pointer is NULL";
+        case LASP2_ERR_SHAPE: return "unsupported or inconsistent shape (B,H,N,d,C,L)";
+        case LASP2_ERR_DTYPE: return "unsupported dtype";
+        case LASP2_ERR_SEQLENS: return "invalid packed-sequence offsets";
+        case LASP2_ERR_WORKSPACE: return "workspace too small";
+        case LASP2_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case LASP2_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Internal declarations shared by the host dispatch and the kernel files of
+// liblasp2.  Nothing here is part of the public ABI (that is include/lasp2.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lasp2.h"
+
+namespace lasp2 {
+
+// Problem geometry handed by value to every kernel.
+struct Geom {
+    int32_t G;            // B*H independent (batch, head) groups
+    int32_t N;            // tokens per group
+    int32_t d;            // head dimension
+    int32_t C;            // chunk length
+    int64_t L;            // tokens per state slot (multiple of C)
+    int32_t T_s;          // slots per group
+    int32_t n_seqs;       // packed: number of documents; 0 = not packed
+    const int32_t* cu;    // packed: DEVICE pointer to n_seqs+1 offsets
+};
+
+// Token range [tok0, tok0+len) of slot s.  Unpacked: direct.  Packed: walk the
+// documents (uniform scalar loads; n_seqs is small next to the work per slot).
+__device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int& len)
+{
+    if (g.n_seqs == 0) {
+        int64_t a = (int64_t)s * g.L;
+        int64_t b = a + g.L;
+        if (b > g.N) b = g.N;
+        tok0 = (int)a;
+        len = (int)(b - a);
+        return;
+    }
+    int base = 0;
+    tok0 = 0;
+    len = 0;
+    for (int k = 0; k < g.n_seqs; ++k) {
+        int a = g.cu[k], b = g.cu[k + 1];
+        int ns = (int)(((int64_t)(b - a) + g.L - 1) / g.L);
+        if (s < base + ns) {
+            int64_t t0 = (int64_t)a + (int64_t)(s - base) * g.L;
+            int64_t t1 = t0 + g.L;
+            if (t1 > b) t1 = b;
+            tok0 = (int)t0;
+            len = (int)(t1 - t0);
+            return;
+        }
+        base += ns;
+    }
+}
+
+// ---- launchers implemented in the kernel files (return hipGetLastError()) ----
+
+// Plain fp32-FMA kernels, any supported (dtype, d, C).
+hipError_t launch_states_generic(const Geom& g, int dtype, const void* K, const void* V,
+                                 float* M, hipStream_t st);
+// out = [(A Bk^T) (.) mask] Cv + A * state, state += Bk^T Cv chunk by chunk.
+//   reverse = 0: causal mask, chunks walked first to last, state = prefix;
+//   reverse = 1: anti-causal mask (j >= i), chunks walked last to first, state = suffix.
+//   transpose_state: the d x d slot state is read transposed.
+hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const void* Bk,
+                               const void* Cv, const float* state, void* out,
+                               int transpose_state, int reverse, hipStream_t st);
+hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse,
+                               hipStream_t st);
+
+// bf16 MFMA kernels (d = 128, C in {64,128,256}).
+bool mfma_path_supported(const Geom& g, int dtype);
+hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
+                              hipStream_t st);
+hipError_t launch_attn_mfma(const Geom& g, const void* A, const void* Bk, const void* Cv,
+                            const float* state, void* out, int transpose_state, int reverse,
+                            hipStream_t st);
+
+}  // namespace lasp2

@@ -1,0 +1,121 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol that
+include/lasp2.h declares, and every argument error is reported before any device work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_07563_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: the calls below fail earlier
+ODD = ctypes.c_void_p(0x1004)
+
+
+def _desc(**kw):
+    base = dict(B=1, H=2, N=1024, d=64, C=128, L=0, dtype=B.LASP2_F32, n_seqs=0,
+                cu_seqlens_host=None, cu_seqlens_dev=None)
+    base.update(kw)
+    return B.Desc(**base)
+
+
+def _slots(desc):
+    out = ctypes.c_int64(-1)
+    rc = B.lib().lasp2_num_slots(ctypes.byref(desc), ctypes.byref(out))
+    return rc, out.value
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "lasp2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(lasp2_[a-z0-9_]+)\s*\(", text))
+    assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
+            "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string"} <= names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lasp2.h but not exported"
+
+
+def test_status_strings():
+    for code in range(0, -8, -1):
+        assert B.status_string(code) and B.status_string(code) != "unknown status"
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_num_slots_unpacked():
+    assert _slots(_desc()) == (0, 8)
+    assert _slots(_desc(N=1000)) == (0, 8)                       # ragged tail
+    assert _slots(_desc(N=262144, d=128, C=256, L=4096, H=16, dtype=B.LASP2_BF16)) == (0, 64)
+    assert _slots(_desc(N=5, L=512)) == (0, 1)                   # slot longer than the sequence
+    assert _slots(_desc(N=0)) == (0, 0)                          # empty problem
+
+
+def test_num_slots_packed_matches_rule():
+    cu = np.array([0, 64, 300, 301, 1024], dtype=np.int32)
+    for L, C in ((128, 128), (256, 128), (512, 64)):
+        want = int(sum(-(-int(n) // L) for n in np.diff(cu)))
+        d = _desc(C=C, L=L, n_seqs=4, cu_seqlens_host=cu.ctypes.data, cu_seqlens_dev=0x2000)
+        assert _slots(d) == (0, want)
+
+
+def test_workspace_size():
+    out = ctypes.c_size_t(0)
+    d = _desc(B=8, H=32, N=8192, d=128, C=256, dtype=B.LASP2_BF16)
+    assert B.lib().lasp2_workspace_size(ctypes.byref(d), ctypes.byref(out)) == 0
+    assert out.value == 8 * 32 * 32 * 128 * 128 * 4
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=48), -2), (dict(d=256), -2), (dict(C=0), -2), (dict(C=513), -2), (dict(N=-1), -2),
+    (dict(L=100), -2), (dict(L=-128), -2), (dict(B=70000, H=1), -2),
+    (dict(dtype=7), -3),
+    (dict(n_seqs=-1), -4),
+])
+def test_shape_errors(kw, code):
+    assert _slots(_desc(**kw))[0] == code
+
+
+def test_seqlens_errors():
+    good = np.array([0, 100, 1024], dtype=np.int32)
+    mk = lambda cu, **kw: _desc(n_seqs=len(cu) - 1, cu_seqlens_host=cu.ctypes.data,
+                                cu_seqlens_dev=0x2000, **kw)
+    assert _slots(mk(good))[0] == 0
+    assert _slots(mk(good, B=2))[0] == -4                                   # packed needs B == 1
+    assert _slots(mk(np.array([1, 100, 1024], dtype=np.int32)))[0] == -4    # cu[0] != 0
+    assert _slots(mk(np.array([0, 100, 1000], dtype=np.int32)))[0] == -4    # cu[n] != N
+    assert _slots(mk(np.array([0, 100, 100, 1024], dtype=np.int32)))[0] == -4  # empty document
+    assert _slots(mk(np.array([0, 200, 100, 1024], dtype=np.int32)))[0] == -4  # not monotone
+    assert _slots(_desc(n_seqs=2, cu_seqlens_host=good.ctypes.data))[0] == -4  # device copy missing
+    assert _slots(_desc(cu_seqlens_dev=0x2000))[0] == -4                    # offsets without n_seqs
+
+
+def test_null_and_alignment_errors_reach_no_device():
+    lib, d = B.lib(), _desc()
+    r = ctypes.byref(d)
+    assert lib.lasp2_num_slots(None, ctypes.byref(ctypes.c_int64())) == -1
+    assert lib.lasp2_num_slots(r, None) == -1
+    assert lib.lasp2_chunk_states(r, None, FAKE, FAKE, None) == -1
+    assert lib.lasp2_chunk_states(r, FAKE, ODD, FAKE, None) == -6
+    assert lib.lasp2_state_prefix(r, FAKE, None, 0, None) == -1
+    assert lib.lasp2_state_prefix(r, ODD, FAKE, 0, None) == -6
+    assert lib.lasp2_attn_fwd(r, FAKE, FAKE, FAKE, None, FAKE, None) == -1
+    assert lib.lasp2_attn_fwd(r, FAKE, FAKE, FAKE, FAKE, ODD, None) == -6
+    args = [FAKE] * 9
+    for i in range(9):
+        a = list(args); a[i] = None
+        assert lib.lasp2_attn_bwd(r, *a, ctypes.c_size_t(1 << 40), None) == -1
+    need = ctypes.c_size_t(0)
+    lib.lasp2_workspace_size(r, ctypes.byref(need))
+    assert lib.lasp2_attn_bwd(r, *args, ctypes.c_size_t(need.value - 1), None) == -5
+
+
+def test_empty_problem_is_ok_without_pointers():
+    lib = B.lib()
+    for kw in (dict(N=0), dict(B=0), dict(H=0)):
+        r = ctypes.byref(_desc(**kw))
+        assert lib.lasp2_chunk_states(r, None, None, None, None) == 0
+        assert lib.lasp2_state_prefix(r, None, None, 0, None) == 0
+        assert lib.lasp2_attn_fwd(r, None, None, None, None, None, None) == 0
+        assert lib.lasp2_attn_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0

@@ -1,0 +1,135 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element,
+on the same seeded inputs.  Sizes here are ones the brute-force oracle finishes in seconds;
+they span several chunks, several slots and ragged tails."""
+import numpy as np
+import pytest
+
+from tests.util import TOL, TOL_STATE, host_inputs, rel_l2, slot_partition, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_all(oracle, B, H, N, d, C, L, dtype, seed, cu=None, check_bwd=True):
+    import torch
+    from paper_2502_07563_amd import binding as bd
+
+    G = B * H
+    x = host_inputs(seed, G, N, d, dtype)
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu)
+    Leff = L if L else C
+    bounds, first = slot_partition(N, Leff, cu)
+    assert bd.lasp2_num_slots(p) == len(first)
+
+    Q, K, V, dO = (to_device(x[n], B, H, dtype) for n in ("Q", "K", "V", "dO"))
+    M = bd.alloc_states(p)
+    P = torch.empty_like(M)
+    O = torch.full_like(Q, float("nan"))
+    bd.lasp2_chunk_states(p, K, V, M)
+    bd.lasp2_state_prefix(p, M, P, False)
+    bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+    torch.cuda.synchronize()
+
+    x64 = {k: v.astype(np.float64) for k, v in x.items()}
+    errs = {}
+    M_ref = oracle.chunk_states(x64["K"], x64["V"], bounds)
+    P_ref = oracle.state_prefix(M_ref, first, reverse=False)
+    errs["M"] = rel_l2(to_host(M), M_ref)
+    errs["P"] = rel_l2(to_host(P), P_ref)
+    O_ref = oracle.fwd_def(x64["Q"], x64["K"], x64["V"], cu)
+    errs["O"] = rel_l2(to_host(O), O_ref)
+    assert errs["M"] <= TOL_STATE and errs["P"] <= TOL_STATE, errs
+    assert errs["O"] <= TOL[dtype], errs
+
+    if check_bwd:
+        dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+        ws = torch.empty_like(M)
+        bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
+        torch.cuda.synchronize()
+        dQ_ref, dK_ref, dV_ref = oracle.bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu)
+        dP_ref = oracle.state_prefix(oracle.chunk_states(x64["Q"], x64["dO"], bounds), first, reverse=True)
+        errs["dP"] = rel_l2(to_host(ws), dP_ref)
+        errs["dQ"] = rel_l2(to_host(dQ), dQ_ref)
+        errs["dK"] = rel_l2(to_host(dK), dK_ref)
+        errs["dV"] = rel_l2(to_host(dV), dV_ref)
+        assert errs["dP"] <= TOL_STATE, errs
+        for k in ("dQ", "dK", "dV"):
+            assert errs[k] <= TOL[dtype], errs
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    return errs
+
+
+def test_cfg1_fp32_forward(oracle):
+    """Config 1 exactly: fp32, B=1, H=2, N=1024, d=64, C=128 (8 chunks), seed 0."""
+    _run_all(oracle, 1, 2, 1024, 64, 128, 0, "f32", seed=0, check_bwd=True)
+
+
+@pytest.mark.parametrize("N,d,C,L", [(1000, 32, 128, 256), (777, 16, 50, 150), (300, 64, 512, 0),
+                                     (5, 16, 1, 2), (1, 16, 8, 0), (130, 128, 64, 128)])
+def test_fp32_shapes(oracle, N, d, C, L):
+    _run_all(oracle, 2, 2, N, d, C, L, "f32", seed=10 + N)
+
+
+@pytest.mark.parametrize("N,C,L", [(2048, 256, 0), (2304, 256, 1024), (1900, 256, 512), (200, 256, 0),
+                                   (1536, 128, 512), (1000, 64, 256)])
+def test_bf16_d128(oracle, N, C, L):
+    """The MFMA path's shapes (bf16, d=128): several chunks per slot, ragged tails."""
+    _run_all(oracle, 1, 3, N, 128, C, L, "bf16", seed=20 + N)
+
+
+def test_bf16_generic_shapes(oracle):
+    _run_all(oracle, 1, 2, 600, 64, 128, 256, "bf16", seed=31)
+    _run_all(oracle, 1, 2, 333, 128, 96, 192, "bf16", seed=32)
+
+
+@pytest.mark.parametrize("dtype,d,C,L", [("bf16", 128, 256, 0), ("bf16", 128, 256, 512),
+                                         ("f32", 32, 64, 128)])
+def test_packed_documents(oracle, dtype, d, C, L):
+    """Packed batch: boundaries not aligned to C, documents shorter than C and of length 1."""
+    lens = [64, 700, 1, 255, 256, 257, 1467, 3]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _run_all(oracle, 1, 2, int(cu[-1]), d, C, L, dtype, seed=40, cu=cu)
+
+
+def test_prefix_in_place_and_deterministic(oracle):
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    p = bd.Problem(1, 2, 4096, 128, 256, 0, "bf16")
+    x = host_inputs(50, 2, 4096, 128, "bf16")
+    Q, K, V, dO = (to_device(x[n], 1, 2, "bf16") for n in ("Q", "K", "V", "dO"))
+    runs = []
+    for _ in range(2):
+        M = bd.alloc_states(p)
+        bd.lasp2_chunk_states(p, K, V, M)
+        P = torch.empty_like(M)
+        bd.lasp2_state_prefix(p, M, P, False)
+        bd.lasp2_state_prefix(p, M, M, False)          # in place
+        torch.cuda.synchronize()
+        assert torch.equal(M, P)
+        O = torch.empty_like(Q)
+        bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+        dQ, dK, dV, dP = bd.backward(p, Q, K, V, dO, P)
+        torch.cuda.synchronize()
+        runs.append((P, O, dQ, dK, dV, dP))
+    for a, b in zip(*runs):
+        assert torch.equal(a, b), "not run-to-run bit-identical"
+
+
+def test_result_does_not_depend_on_C_or_L(oracle):
+    """Chunk length and slot length change the schedule, not the result (within tolerance)."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    N = 3072
+    x = host_inputs(60, 2, N, 128, "bf16")
+    Q, K, V, dO = (to_device(x[n], 1, 2, "bf16") for n in ("Q", "K", "V", "dO"))
+    ref = None
+    for C, L in ((256, 0), (256, 1024), (256, 3072), (128, 512), (64, 64)):
+        p = bd.Problem(1, 2, N, 128, C, L, "bf16")
+        O, P = bd.forward(p, Q, K, V)
+        dQ, dK, dV, _ = bd.backward(p, Q, K, V, dO, P)
+        torch.cuda.synchronize()
+        got = [to_host(t) for t in (O, dQ, dK, dV)]
+        if ref is None:
+            ref = got
+        else:
+            for a, b in zip(got, ref):
+                assert rel_l2(a, b) <= TOL["bf16"]
