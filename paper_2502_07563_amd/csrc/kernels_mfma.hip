@@ -190,9 +190,74 @@ __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* 
 // Fused attention pass over one slot:
 //   out_c = [(A_c Bk_c^T) (.) mask] Cv_c + A_c S_c ,   S_{c+1} = S_c + Bk_c^T Cv_c
 // with S starting from the slot's prefix (or suffix) state.  C/32 waves; wave w owns 32
-// rows of the chunk for the whole chunk; the chunk's keys/values stream through LDS in
+// rows of the chunk for the whole chunk; the chunk's Bk/Cv rows stream through LDS in
 // 64-token stages shared by all waves; every wave also owns 16/NW tiles of the state.
+//
+// Staging: global_load_lds_dwordx4 writes each lane's 16 bytes straight into LDS at
+// (M0 base) + 16*lane, so a wave instruction fills four 256-byte tile rows; the swizzle
+// is applied on the global side (lane -> which 16 bytes it fetches).  A ring of three
+// stages keeps two blocks (64 KiB) in flight per workgroup while a third is consumed.
+// The loads are issued from inline asm, invisible to the compiler's wait-count
+// tracking, and are retired by explicit s_waitcnt vmcnt(n): each wave issues DPS loads
+// per stage, memory operations retire in order, and at least the DPS loads of the next
+// stage were issued after those of the stage about to be read, so vmcnt(DPS) is always
+// sufficient (extra loads or stores issued in between only make the wait stricter).
 // =====================================================================================
+constexpr int NSTAGE = 3;
+
+__device__ __forceinline__ uint32_t lds_addr_of(const char* p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+__device__ __forceinline__ void dma16(const char* gptr, uint32_t lds_base)
+{
+    // lds_base is the same in every lane of the wave; readfirstlane moves it to a scalar register
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Issue the loads of one 64-token block (rows tok .. tok+63 of the slot) of X and Y into the
+// stage tiles tx, ty.  Rows past the slot's end are fetched from its last row (always in
+// bounds) and zeroed afterwards by zero_tail_rows().
+template <int NW>
+__device__ __forceinline__ void dma_block(const char* X, const char* Y, size_t row0_bytes, int tok,
+                                          int len, char* tx, char* ty, int w, int lane)
+{
+    constexpr int IPW = 16 / NW;   // wave instructions per tensor per stage
+#pragma unroll
+    for (int u = 0; u < IPW; ++u) {
+        const int rowbase = 4 * (w * IPW + u);
+        const int r = rowbase + (lane >> 4);
+        const int lc = (lane & 15) ^ swz(r);
+        const int gr = min(tok + r, len - 1);
+        const size_t off = row0_bytes + (size_t)gr * ROWB + lc * 16;
+        dma16(X + off, lds_addr_of(tx + rowbase * ROWB));
+        dma16(Y + off, lds_addr_of(ty + rowbase * ROWB));
+    }
+}
+
+template <int NW>
+__device__ __forceinline__ void zero_tail_rows(int tok, int len, char* tx, char* ty, int w, int lane)
+{
+    constexpr int IPW = 16 / NW;
+#pragma unroll
+    for (int u = 0; u < IPW; ++u) {
+        const int r = 4 * (w * IPW + u) + (lane >> 4);
+        if (tok + r >= len) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(tx + r * ROWB + (lane & 15) * 16) = z;
+            *reinterpret_cast<u32x4*>(ty + r * ROWB + (lane & 15) * 16) = z;
+        }
+    }
+}
+
 template <int C>
 __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __restrict__ A,
                                                           const char* __restrict__ Bk,
@@ -201,23 +266,42 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
                                                           char* __restrict__ out,
                                                           int transpose_state, int reverse)
 {
-    constexpr int NW = C / 32, NT = NW * 64, TPW = 16 / NW;
+    constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB;
+    constexpr int DPS = 2 * (16 / NW);     // loads per wave per stage
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* sK = smem;                       // Bk stages
-    char* sV = smem + 2 * STAGE_BYTES;     // Cv stages
-    char* sM = smem + 4 * STAGE_BYTES;     // state snapshot, bf16 [d_v][d_k]
+    char* sK = smem;                              // Bk stages
+    char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
+    char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
     const int s = blockIdx.x, grp = blockIdx.y;
     int tok0, len;
     slot_range(g, s, tok0, len);
+    if (len <= 0) return;
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
 
     // Row block of this wave.  With 8 waves, waves w and w+4 (which share a SIMD under
     // round-robin placement) get blocks s and 7-s, so that their triangular work adds up evenly.
     const int rb = (NW == 8) ? (w < 4 ? w : 11 - w) : w;
     const int t0 = w * TPW;
+
+    const int nch = (len + C - 1) / C;
+    const int nblk_tail = ((len - (nch - 1) * C) + KB - 1) / KB;   // blocks of the (ragged) last chunk
+    const int NB = (nch - 1) * BPC + nblk_tail;                     // blocks in the whole slot
+    // slot-relative first token of the i-th block in walk order
+    auto tok_of = [&](int i) -> int {
+        if (!reverse) return i * KB;
+        if (i < nblk_tail) return (nch - 1) * C + i * KB;
+        const int j = i - nblk_tail;
+        return (nch - 2 - j / BPC) * C + (j % BPC) * KB;
+    };
+    auto issue = [&](int i) {
+        dma_block<NW>(Bk, Cv, row0, tok_of(i), len, sK + (i % NSTAGE) * STAGE_BYTES,
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane);
+    };
+    issue(0);
+    if (NB > 1) issue(1);
 
     // running state tiles, C/D layout: rows = d_k (first index), columns = d_v
     f32x16 Macc[TPW];
@@ -241,8 +325,6 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
         }
     }
 
-    const int nch = (len + C - 1) / C;
-    BlockRegs<NT> regs;
     bf16x8 qf[8];   // this wave's 32 rows of A as B-operand fragments (column = row of A, k = d)
     auto load_q = [&](int c) {
         const int r = c * C + 32 * rb + l32;
@@ -255,22 +337,19 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
             qf[ks] = __builtin_bit_cast(bf16x8, x);
         }
     };
-    {
-        const int c = reverse ? nch - 1 : 0;
-        load_block<NT>(regs, Bk, Cv, row0, c * C, len, tid);
-        load_q(c);
-    }
+    load_q(reverse ? nch - 1 : 0);
 
-    int blkcount = 0;
+    int bi = 0;          // index of the block being consumed, in walk order
+    int prev_nblk = 0;
     for (int ci = 0; ci < nch; ++ci) {
         const int c = reverse ? nch - 1 - ci : ci;
         const int cn = reverse ? c - 1 : c + 1;          // next chunk in walk order
-        const int clen = min(C, len - c * C);
-        const int nblk = (clen + KB - 1) / KB;
+        const int nblk = (c == nch - 1) ? nblk_tail : BPC;
         const bool last_chunk = (ci + 1 == nch);
 
-        // all waves are done reading the previous snapshot and both stages
-        __syncthreads();
+        // The previous chunk read the snapshot in its first block; a later block barrier has
+        // separated that from this write unless the chunk had a single block.
+        if (ci > 0 && prev_nblk < 2) __syncthreads();
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
             const int t = t0 + u, a = t >> 2, b = t & 3;
@@ -288,13 +367,15 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
 #pragma unroll
             for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
 
-        for (int jb = 0; jb < nblk; ++jb) {
-            char* tK = sK + (blkcount & 1) * STAGE_BYTES;
-            char* tV = sV + (blkcount & 1) * STAGE_BYTES;
-            store_block<NT>(regs, tK, tV, tid);
-            if (jb + 1 < nblk) load_block<NT>(regs, Bk, Cv, row0, c * C + (jb + 1) * KB, len, tid);
-            else if (!last_chunk) load_block<NT>(regs, Bk, Cv, row0, cn * C, len, tid);
-            __syncthreads();
+        for (int jb = 0; jb < nblk; ++jb, ++bi) {
+            char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
+            char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+            // this wave's loads of block bi have landed (those of bi+1 may still fly)
+            if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            const int tok = tok_of(bi);
+            if (tok + KB > len) zero_tail_rows<NW>(tok, len, tK, tV, w, lane);
+            __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
+            if (bi + 2 < NB) issue(bi + 2);
 
             if (jb == 0) {
                 // inter-chunk term: out^T += S^T A^T  with S^T = snapshot [d_v][d_k]
@@ -341,8 +422,8 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
             // the rows of the next chunk replace qf while the state update and the store run
             if (jb + 1 == nblk && !last_chunk) load_q(cn);
             if (!last_chunk) update_tiles<TPW>(Macc, tK, tV, t0, lane);
-            ++blkcount;
         }
+        prev_nblk = nblk;
 
         // out rows of this wave: lane owns query row l32, 4 consecutive d_v per (tv, q)
         {
@@ -366,7 +447,7 @@ template <int C>
 hipError_t launch_attn_C(const Geom& g, const void* A, const void* Bk, const void* Cv,
                          const float* state, void* out, int tr, int rev, hipStream_t st)
 {
-    constexpr int smem = 4 * STAGE_BYTES + D * ROWB;   // 96 KiB
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB;   // 128 KiB
     auto kern = attn_mfma_kernel<C>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
