@@ -62,6 +62,28 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const char* tile, int rowA, int r
     return __builtin_bit_cast(bf16x8, both);
 }
 
+// The swizzle depends on row % 16 only, so a lane's byte offset inside a tile can be computed
+// once and reused for every tile, stage and 16-row step by adding a constant: the helpers below
+// read at (tile + constant) + precomputed lane offset.
+__device__ __forceinline__ int tr_off(int row, int col)
+{
+    return tile_off(row, col >> 3) + (col & 7) * 2;
+}
+
+__device__ __forceinline__ bf16x8 lds_read16_at(const char* base, int lane_off)
+{
+    return *reinterpret_cast<const bf16x8*>(base + lane_off);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr8_at(const char* base, int off_lo, int off_hi)
+{
+    typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + off_lo));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + off_hi));
+    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -258,6 +280,72 @@ __device__ __forceinline__ void zero_tail_rows(int tok, int len, char* tx, char*
     }
 }
 
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Per-lane byte offsets into a swizzled tile, computed once per kernel.
+template <int TPW>
+struct LaneOffs {
+    int nat[8];        // row l32, 16-byte piece holding d = 16 ks + 8h .. +7
+    int pv[4][2];      // transposed fetch of columns 32 tv + l32: rows 4h.. (lo) and 8 + 4h.. (hi)
+    int ua[2];         // state update, X^T operand: columns 32 a + l32, rows 8h.. (lo), 8h + 4.. (hi)
+    int ub[TPW][2];    // state update, Y operand of tile u: columns 32 b_u + l32
+};
+
+template <int TPW>
+__device__ __forceinline__ void make_lane_offs(LaneOffs<TPW>& o, int lane, int t0)
+{
+    const int h = lane >> 5, l32 = lane & 31, i = lane & 15, g2 = (lane >> 4) & 1;
+    const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) o.nat[ks] = tile_off(l32, 2 * ks + h);
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv) {
+        o.pv[tv][0] = tr_off(4 * h + rl, 32 * tv + cl);
+        o.pv[tv][1] = tr_off(8 + 4 * h + rl, 32 * tv + cl);
+    }
+    o.ua[0] = tr_off(8 * h + rl, 32 * (t0 >> 2) + cl);
+    o.ua[1] = tr_off(8 * h + 4 + rl, 32 * (t0 >> 2) + cl);
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) {
+        o.ub[u][0] = tr_off(8 * h + rl, 32 * ((t0 + u) & 3) + cl);
+        o.ub[u][1] = tr_off(8 * h + 4 + rl, 32 * ((t0 + u) & 3) + cl);
+    }
+}
+
+// inter-chunk operands: rows 32 tv + l32 of the snapshot for d_k step ks
+template <int NOP>
+__device__ __forceinline__ void rd_inter(bf16x8 (&buf)[NOP], const char* sM, int nat_ks)
+{
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv) buf[tv] = lds_read16_at(sM + tv * (32 * ROWB), nat_ks);
+}
+
+template <int NOP>
+__device__ __forceinline__ void mm_inter(f32x16 (&Oacc)[4], const bf16x8 (&buf)[NOP], bf16x8 q)
+{
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(buf[tv], q, Oacc[tv]);
+}
+
+// state-update operands for 16-token step ks of a stage: buf[0] = X^T rows of the wave's tile
+// row a, buf[1 + u] = Y columns of tile u (all of a wave's tiles share a).
+template <int TPW, int NOP>
+__device__ __forceinline__ void rd_update(bf16x8 (&buf)[NOP], const char* tx, const char* ty, int ks,
+                                          const LaneOffs<TPW>& o)
+{
+    static_assert(TPW + 1 <= NOP, "operand buffer too small");
+    buf[0] = lds_read_tr8_at(tx + ks * (16 * ROWB), o.ua[0], o.ua[1]);
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) buf[1 + u] = lds_read_tr8_at(ty + ks * (16 * ROWB), o.ub[u][0], o.ub[u][1]);
+}
+
+template <int TPW, int NOP>
+__device__ __forceinline__ void mm_update(f32x16 (&acc)[TPW], const bf16x8 (&buf)[NOP])
+{
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) acc[u] = mfma(buf[0], buf[1 + u], acc[u]);
+}
+
 template <int C>
 __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __restrict__ A,
                                                           const char* __restrict__ Bk,
@@ -268,6 +356,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
 {
     constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB;
     constexpr int DPS = 2 * (16 / NW);     // loads per wave per stage
+    constexpr int NOP = (TPW + 1 > 4) ? 8 : 4;   // operands per register buffer
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* sK = smem;                              // Bk stages
     char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
@@ -325,6 +414,9 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
         }
     }
 
+    LaneOffs<TPW> lo;
+    make_lane_offs<TPW>(lo, lane, t0);
+
     bf16x8 qf[8];   // this wave's 32 rows of A as B-operand fragments (column = row of A, k = d)
     auto load_q = [&](int c) {
         const int r = c * C + 32 * rb + l32;
@@ -340,16 +432,12 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
     load_q(reverse ? nch - 1 : 0);
 
     int bi = 0;          // index of the block being consumed, in walk order
-    int prev_nblk = 0;
     for (int ci = 0; ci < nch; ++ci) {
         const int c = reverse ? nch - 1 - ci : ci;
         const int cn = reverse ? c - 1 : c + 1;          // next chunk in walk order
         const int nblk = (c == nch - 1) ? nblk_tail : BPC;
         const bool last_chunk = (ci + 1 == nch);
 
-        // The previous chunk read the snapshot in its first block; a later block barrier has
-        // separated that from this write unless the chunk had a single block.
-        if (ci > 0 && prev_nblk < 2) __syncthreads();
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
             const int t = t0 + u, a = t >> 2, b = t & 3;
@@ -377,13 +465,25 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
             __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
             if (bi + 2 < NB) issue(bi + 2);
 
+            // Operand fetches are issued a batch ahead of the MFMAs that consume them (two
+            // small register buffers); sched_barrier keeps the compiler from sinking the
+            // reads back next to their uses.
+            bf16x8 bufA[NOP], bufB[NOP];
             if (jb == 0) {
                 // inter-chunk term: out^T += S^T A^T  with S^T = snapshot [d_v][d_k]
+                rd_inter<NOP>(bufA, sM, lo.nat[0]);
+                SCHED_FENCE();
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                    for (int tv = 0; tv < 4; ++tv)
-                        Oacc[tv] = mfma(lds_read16(sM, 32 * tv + l32, 2 * ks + h), qf[ks], Oacc[tv]);
+                for (int ks = 0; ks < 8; ks += 2) {
+                    rd_inter<NOP>(bufB, sM, lo.nat[ks + 1]);
+                    SCHED_FENCE();
+                    mm_inter<NOP>(Oacc, bufA, qf[ks]);
+                    SCHED_FENCE();
+                    if (ks + 2 < 8) rd_inter<NOP>(bufA, sM, lo.nat[ks + 2]);
+                    SCHED_FENCE();
+                    mm_inter<NOP>(Oacc, bufB, qf[ks + 1]);
+                    SCHED_FENCE();
+                }
             }
 
 #pragma unroll
@@ -391,13 +491,30 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
                 const int kt = 2 * jb + half;      // 32-key tile index inside the chunk
                 const bool active = reverse ? (kt >= rb) : (kt <= rb);
                 if (!active) continue;
-                // scores^T (keys x queries) = Bk_tile A_w^T
+                // scores^T (keys x queries) = Bk_tile A_w^T ; the Cv operands of the second
+                // product are fetched while the first one runs
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks]);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks + 4]);
+                SCHED_FENCE();
                 f32x16 sc;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sc[v] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    sc = mfma(lds_read16(tK, 32 * half + l32, 2 * ks + h), qf[ks], sc);
+                for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+                    bufA[tv] = lds_read_tr8_at(tV + half * (32 * ROWB), lo.pv[tv][0], lo.pv[tv][1]);
+                SCHED_FENCE();
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+                    bufB[tv] = lds_read_tr8_at(tV + half * (32 * ROWB) + 16 * ROWB, lo.pv[tv][0], lo.pv[tv][1]);
+                SCHED_FENCE();
                 if (kt == rb) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
@@ -407,39 +524,71 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
                     }
                 }
                 // out^T (d_v x queries) += Cv_tile^T scores^T ; k-slots follow the C/D row order
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    u32x4 pk = {pack2(sc[8 * k2 + 0], sc[8 * k2 + 1]), pack2(sc[8 * k2 + 2], sc[8 * k2 + 3]),
-                                pack2(sc[8 * k2 + 4], sc[8 * k2 + 5]), pack2(sc[8 * k2 + 6], sc[8 * k2 + 7])};
+                {
+                    u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
                     bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
-                    const int rA = 32 * half + 16 * k2 + 4 * h, rB = rA + 8;
 #pragma unroll
-                    for (int tv = 0; tv < 4; ++tv)
-                        Oacc[tv] = mfma(lds_read_tr8(tV, rA, rB, 32 * tv, lane), sb, Oacc[tv]);
+                    for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
                 }
+                {
+                    u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                    bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                    for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+                }
+                SCHED_FENCE();
             }
 
             // the rows of the next chunk replace qf while the state update and the store run
             if (jb + 1 == nblk && !last_chunk) load_q(cn);
-            if (!last_chunk) update_tiles<TPW>(Macc, tK, tV, t0, lane);
-        }
-        prev_nblk = nblk;
-
-        // out rows of this wave: lane owns query row l32, 4 consecutive d_v per (tv, q)
-        {
-            const int r = c * C + 32 * rb + l32;
-            if (r < len) {
-                char* p = out + row0 + (size_t)r * ROWB + 8 * h;
-#pragma unroll
-                for (int tv = 0; tv < 4; ++tv)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        u32x2 pk = {pack2(Oacc[tv][4 * q], Oacc[tv][4 * q + 1]),
-                                    pack2(Oacc[tv][4 * q + 2], Oacc[tv][4 * q + 3])};
-                        *reinterpret_cast<u32x2*>(p + 64 * tv + 16 * q) = pk;
-                    }
+            if (!last_chunk) {
+                // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
+                rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufB, tK, tV, 1, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufA);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufA, tK, tV, 2, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufB);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufB, tK, tV, 3, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufA);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufB);
             }
         }
+
+        // Store this wave's 32 output rows.  The accumulators hold out^T (lane = row, four
+        // consecutive d_v per register group); they are transposed through a wave-private
+        // 4 KiB piece of the snapshot area, half of d_v at a time, so that every lane stores
+        // 16 contiguous bytes and a wave instruction covers whole 128-byte line halves.
+        if (nblk < 2) __syncthreads();   // some wave may still read the snapshot in block 0
+        {
+            char* stg = sM + w * 4096;
+            const int rbase = c * C + 32 * rb;
+#pragma unroll
+            for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+                for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16& o = Oacc[2 * hv + tvv];
+                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                        *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                    if (rbase + row < len)
+                        *reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                }
+            }
+        }
+        if (!last_chunk) __syncthreads();   // staging reads done before the next snapshot write
     }
 }
 
