@@ -346,13 +346,24 @@ __device__ __forceinline__ void mm_update(f32x16 (&acc)[TPW], const bf16x8 (&buf
     for (int u = 0; u < TPW; ++u) acc[u] = mfma(buf[0], buf[1 + u], acc[u]);
 }
 
+// One problem instance for the fused attention pass (see launch_attn_mfma).
+struct AttnProblem {
+    const char* A;        // rows that receive an output ("queries" of this problem)
+    const char* Bk;       // rows scored against A
+    const char* Cv;       // rows mixed by the scores
+    const float* state;   // [G][T_s][d][d] prefix or suffix states
+    char* out;
+    int transpose_state;
+    int reverse;
+};
+
+// nprob == 1: blockIdx.x is the slot.  nprob == 2: two problems that stream the same pair of
+// tensors (dV and dK of the backward both stream Q and dO) share one launch; workgroup x
+// handles slot 8*(x/16) + x%8 of problem (x/8)%2, so that, with workgroups dealt to the
+// eight XCDs round-robin, the two readers of a block run on the same XCD at about the same
+// time and the second one finds it in that XCD's L2.
 template <int C>
-__global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __restrict__ A,
-                                                          const char* __restrict__ Bk,
-                                                          const char* __restrict__ Cv,
-                                                          const float* __restrict__ state,
-                                                          char* __restrict__ out,
-                                                          int transpose_state, int reverse)
+__global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1, int nprob)
 {
     constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB;
     constexpr int DPS = 2 * (16 / NW);     // loads per wave per stage
@@ -364,7 +375,20 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int s = blockIdx.x, grp = blockIdx.y;
+    int s = blockIdx.x, prob = 0;
+    if (nprob == 2) {
+        s = ((blockIdx.x >> 4) << 3) + (blockIdx.x & 7);
+        prob = (blockIdx.x >> 3) & 1;
+        if (s >= g.T_s) return;
+    }
+    const int grp = blockIdx.y;
+    const char* __restrict__ A = prob ? p1.A : p0.A;
+    const char* __restrict__ Bk = prob ? p1.Bk : p0.Bk;
+    const char* __restrict__ Cv = prob ? p1.Cv : p0.Cv;
+    const float* __restrict__ state = prob ? p1.state : p0.state;
+    char* __restrict__ out = prob ? p1.out : p0.out;
+    const int transpose_state = prob ? p1.transpose_state : p0.transpose_state;
+    const int reverse = prob ? p1.reverse : p0.reverse;
     int tok0, len;
     slot_range(g, s, tok0, len);
     if (len <= 0) return;
@@ -593,19 +617,26 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, const char* __
 }
 
 template <int C>
-hipError_t launch_attn_C(const Geom& g, const void* A, const void* Bk, const void* Cv,
-                         const float* state, void* out, int tr, int rev, hipStream_t st)
+hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1, int nprob,
+                         hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB;   // 128 KiB
     auto kern = attn_mfma_kernel<C>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    dim3 grid(g.T_s, g.G), block(C * 2);
-    hipLaunchKernelGGL(kern, grid, block, smem, st, g, static_cast<const char*>(A),
-                       static_cast<const char*>(Bk), static_cast<const char*>(Cv), state,
-                       static_cast<char*>(out), tr, rev);
+    const unsigned gx = nprob == 2 ? 2u * (((unsigned)g.T_s + 7u) & ~7u) : (unsigned)g.T_s;
+    dim3 grid(gx, g.G), block(C * 2);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, nprob);
     return hipGetLastError();
+}
+
+AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const float* state, void* out,
+                         int transpose_state, int reverse)
+{
+    return AttnProblem{static_cast<const char*>(A), static_cast<const char*>(Bk),
+                       static_cast<const char*>(Cv), state, static_cast<char*>(out), transpose_state,
+                       reverse};
 }
 
 }  // namespace
@@ -631,8 +662,21 @@ hipError_t launch_attn_mfma(const Geom& g, const void* A, const void* Bk, const 
                             const float* state, void* out, int transpose_state, int reverse,
                             hipStream_t st)
 {
-    if (g.C == 256) return launch_attn_C<256>(g, A, Bk, Cv, state, out, transpose_state, reverse, st);
-    return launch_attn_C<128>(g, A, Bk, Cv, state, out, transpose_state, reverse, st);
+    const AttnProblem p = make_problem(A, Bk, Cv, state, out, transpose_state, reverse);
+    if (g.C == 256) return launch_attn_C<256>(g, p, p, 1, st);
+    return launch_attn_C<128>(g, p, p, 1, st);
+}
+
+hipError_t launch_attn_pair_mfma(const Geom& g, const void* A0, const void* A1, const void* X,
+                                 const void* Y, const float* state, void* out0, void* out1,
+                                 int reverse, hipStream_t st)
+{
+    // problem 0: (A0, Bk = X, Cv = Y), state as stored; problem 1: (A1, Bk = Y, Cv = X), whose
+    // state Y^T X is the transpose of the stored X^T Y.
+    const AttnProblem p0 = make_problem(A0, X, Y, state, out0, 0, reverse);
+    const AttnProblem p1 = make_problem(A1, Y, X, state, out1, 1, reverse);
+    if (g.C == 256) return launch_attn_C<256>(g, p0, p1, 2, st);
+    return launch_attn_C<128>(g, p0, p1, 2, st);
 }
 
 }  // namespace lasp2

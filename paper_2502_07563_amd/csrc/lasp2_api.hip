@@ -182,9 +182,12 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     e = run_attn(g, desc->dtype, dO, V, K, P, dQ, 1, 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     // dV: anti-causal problem with (K, Q, dO); state dM_{t+1:T} = sum Q^T dO.
+    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
+    // Both stream Q and dO; the MFMA path runs them as one paired launch.
+    if (mfma_path_supported(g, desc->dtype))
+        return from_hip(launch_attn_pair_mfma(g, K, V, Q, dO, dP, dV, dK, 1, st));
     e = run_attn(g, desc->dtype, K, Q, dO, dP, dV, 0, 1, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
     e = run_attn(g, desc->dtype, V, dO, Q, dP, dK, 1, 1, st);
     return from_hip(e);
 }

@@ -66,12 +66,17 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const vo
 hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse,
                                hipStream_t st);
 
-// bf16 MFMA kernels (d = 128, C in {64,128,256}).
+// bf16 MFMA kernels (d = 128, C in {128,256}).
 bool mfma_path_supported(const Geom& g, int dtype);
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
                               hipStream_t st);
 hipError_t launch_attn_mfma(const Geom& g, const void* A, const void* Bk, const void* Cv,
                             const float* state, void* out, int transpose_state, int reverse,
                             hipStream_t st);
+// Two problems that stream the same tensors X, Y with swapped roles, in one launch:
+//   out0 = attn(A0, Bk = X, Cv = Y, state),  out1 = attn(A1, Bk = Y, Cv = X, state^T).
+hipError_t launch_attn_pair_mfma(const Geom& g, const void* A0, const void* A1, const void* X,
+                                 const void* Y, const float* state, void* out0, void* out1,
+                                 int reverse, hipStream_t st);
 
 }  // namespace lasp2
