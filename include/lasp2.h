@@ -132,7 +132,8 @@ int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
  * In: Q,K,V,dO [B,H,N,d]; P = the forward's cached prefix array (the paper
  * keeps M_{1:t-1} in HBM for this purpose).  Out: dQ,dK,dV [B,H,N,d].
  * `workspace`: device scratch of at least lasp2_workspace_size() bytes,
- * 16-byte aligned; contents on return are the suffix states dM_{t+1:T}.
+ * 16-byte aligned; its contents on return are unspecified (suffix states in
+ * the form the kernels that ran wanted them).
  */
 int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                    const void* V, const void* dO, const float* P,

@@ -154,7 +154,7 @@ def forward(p: Problem, Q, K, V, stream=None):
 
 
 def backward(p: Problem, Q, K, V, dO, P, stream=None):
-    """attn_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, dP)."""
+    """attn_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, workspace)."""
     ws = alloc_states(p, Q.device)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws, stream)

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
 constexpr int kScanBatch = 8;
 
 __global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const float* M, float* P,
-                                                                int reverse)
+                                                                int reverse, int inclusive)
 {
     const int dd = g.d * g.d;
     const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
@@ -188,8 +188,10 @@ __global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const fl
 #pragma unroll
             for (int u = 0; u < kScanBatch; ++u)
                 if (r + u < ns) {
-                    *reinterpret_cast<float4*>(P + base + (size_t)(s + step * u) * dd) = run;
+                    float4* dst = reinterpret_cast<float4*>(P + base + (size_t)(s + step * u) * dd);
+                    if (!inclusive) *dst = run;
                     run.x += m[u].x; run.y += m[u].y; run.z += m[u].z; run.w += m[u].w;
+                    if (inclusive) *dst = run;
                 }
             s += step * min(kScanBatch, ns - r);
         }
@@ -262,11 +264,12 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const vo
                           static_cast<__hip_bfloat16*>(out), transpose_state, reverse, st);
 }
 
-hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, hipStream_t st)
+hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, int inclusive,
+                               hipStream_t st)
 {
     const int dd = g.d * g.d;
     dim3 grid((dd / 4 + kThreads - 1) / kThreads, g.G), block(kThreads);
-    hipLaunchKernelGGL(state_prefix_kernel, grid, block, 0, st, g, M, P, reverse);
+    hipLaunchKernelGGL(state_prefix_kernel, grid, block, 0, st, g, M, P, reverse, inclusive);
     return hipGetLastError();
 }
 

@@ -346,24 +346,76 @@ __device__ __forceinline__ void mm_update(f32x16 (&acc)[TPW], const bf16x8 (&buf
     for (int u = 0; u < TPW; ++u) acc[u] = mfma(buf[0], buf[1 + u], acc[u]);
 }
 
-// One problem instance for the fused attention pass (see launch_attn_mfma).
+// One problem instance for the fused attention pass.
 struct AttnProblem {
     const char* A;        // rows that receive an output ("queries" of this problem)
     const char* Bk;       // rows scored against A
     const char* Cv;       // rows mixed by the scores
-    const float* state;   // [G][T_s][d][d] prefix or suffix states
+    const float* state;   // [G][T_s][d][d] slot states (see `anti`)
     char* out;
-    int transpose_state;
-    int reverse;
+    int transpose_state;  // read the d x d slot state transposed
+    int anti;             // 0: causal (j <= i); 1: anti-causal (j >= i)
 };
 
-// nprob == 1: blockIdx.x is the slot.  nprob == 2: two problems that stream the same pair of
-// tensors (dV and dK of the backward both stream Q and dO) share one launch; workgroup x
-// handles slot 8*(x/16) + x%8 of problem (x/8)%2, so that, with workgroups dealt to the
-// eight XCDs round-robin, the two readers of a block run on the same XCD at about the same
-// time and the second one finds it in that XCD's L2.
+// Snapshot of the running state for the inter-chunk product: bf16 [d_v][d_k] in LDS.
+// negate: the accumulators hold minus the state (anti-causal walk, see the kernel).
+template <int TPW>
+__device__ __forceinline__ void write_snapshot(char* sM, const f32x16 (&Macc)[TPW], int t0, int l32, int h,
+                                               bool negate)
+{
+    const float sg = negate ? -1.f : 1.f;
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) {
+        const int t = t0 + u, a = t >> 2, b = t & 3;
+        const int row = 32 * b + l32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32x2 pk = {pack2(sg * Macc[u][4 * q], sg * Macc[u][4 * q + 1]),
+                        pack2(sg * Macc[u][4 * q + 2], sg * Macc[u][4 * q + 3])};
+            *reinterpret_cast<u32x2*>(sM + tile_off(row, 4 * a + q) + 8 * h) = pk;
+        }
+    }
+}
+
+// inter-chunk term: out^T += S^T A^T with S^T = snapshot [d_v][d_k]; operands of d_k step
+// ks+1 are fetched while the MFMAs of step ks run
+template <int NOP>
+__device__ __forceinline__ void inter_product(f32x16 (&Oacc)[4], const char* sM, const bf16x8 (&qf)[8],
+                                              const int (&nat)[8])
+{
+    bf16x8 bufA[NOP], bufB[NOP];
+    rd_inter<NOP>(bufA, sM, nat[0]);
+    SCHED_FENCE();
+#pragma unroll
+    for (int ks = 0; ks < 8; ks += 2) {
+        rd_inter<NOP>(bufB, sM, nat[ks + 1]);
+        SCHED_FENCE();
+        mm_inter<NOP>(Oacc, bufA, qf[ks]);
+        SCHED_FENCE();
+        if (ks + 2 < 8) rd_inter<NOP>(bufA, sM, nat[ks + 2]);
+        SCHED_FENCE();
+        mm_inter<NOP>(Oacc, bufB, qf[ks + 1]);
+        SCHED_FENCE();
+    }
+}
+
+// The grid carries nprob problems that walk the same slots: workgroup x handles slot
+// 8*(x/(8 nprob)) + x%8 of problem (x/8)%nprob.  With workgroups dealt to the eight XCDs
+// round-robin, the nprob workgroups of a slot land on the same XCD and run at about the same
+// time, so a block of a tensor that several problems stream (the three backward problems all
+// walk forward over Q, K, V, dO) comes from HBM once and from that XCD's L2 afterwards.
+//
+// Walk: chunks in ascending order in both modes.
+//   causal: the accumulators hold S_c = prefix state before chunk c; snapshot and inter-chunk
+//     product at the start of the chunk, then S += Bk_c^T Cv_c.
+//   anti-causal: the slot state handed in is the INCLUSIVE suffix at the slot's start,
+//     R = sum over this and all later slots of the document.  The accumulators hold -R and
+//     add Bk_c^T Cv_c block by block, so after the chunk's own blocks they hold minus the
+//     suffix beyond chunk c, which is the state its rows need; snapshot (negated) and
+//     inter-chunk product therefore come at the end of the chunk.
 template <int C>
-__global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1, int nprob)
+__global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
+                                                          AttnProblem p2, int nprob)
 {
     constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB;
     constexpr int DPS = 2 * (16 / NW);     // loads per wave per stage
@@ -372,23 +424,22 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     char* sK = smem;                              // Bk stages
     char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
     char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
+    char* sO = sM + D * ROWB;                     // output staging, 4 KiB per wave
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    int s = blockIdx.x, prob = 0;
-    if (nprob == 2) {
-        s = ((blockIdx.x >> 4) << 3) + (blockIdx.x & 7);
-        prob = (blockIdx.x >> 3) & 1;
-        if (s >= g.T_s) return;
-    }
+    const int s = (int)(blockIdx.x / (8u * nprob)) * 8 + (int)(blockIdx.x & 7u);
+    const int prob = (int)(blockIdx.x >> 3) % nprob;
+    if (s >= g.T_s) return;
     const int grp = blockIdx.y;
-    const char* __restrict__ A = prob ? p1.A : p0.A;
-    const char* __restrict__ Bk = prob ? p1.Bk : p0.Bk;
-    const char* __restrict__ Cv = prob ? p1.Cv : p0.Cv;
-    const float* __restrict__ state = prob ? p1.state : p0.state;
-    char* __restrict__ out = prob ? p1.out : p0.out;
-    const int transpose_state = prob ? p1.transpose_state : p0.transpose_state;
-    const int reverse = prob ? p1.reverse : p0.reverse;
+    const AttnProblem& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
+    const char* __restrict__ A = pr.A;
+    const char* __restrict__ Bk = pr.Bk;
+    const char* __restrict__ Cv = pr.Cv;
+    const float* __restrict__ state = pr.state;
+    char* __restrict__ out = pr.out;
+    const int transpose_state = pr.transpose_state;
+    const int anti = pr.anti;
     int tok0, len;
     slot_range(g, s, tok0, len);
     if (len <= 0) return;
@@ -400,17 +451,9 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     const int t0 = w * TPW;
 
     const int nch = (len + C - 1) / C;
-    const int nblk_tail = ((len - (nch - 1) * C) + KB - 1) / KB;   // blocks of the (ragged) last chunk
-    const int NB = (nch - 1) * BPC + nblk_tail;                     // blocks in the whole slot
-    // slot-relative first token of the i-th block in walk order
-    auto tok_of = [&](int i) -> int {
-        if (!reverse) return i * KB;
-        if (i < nblk_tail) return (nch - 1) * C + i * KB;
-        const int j = i - nblk_tail;
-        return (nch - 2 - j / BPC) * C + (j % BPC) * KB;
-    };
+    const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
     auto issue = [&](int i) {
-        dma_block<NW>(Bk, Cv, row0, tok_of(i), len, sK + (i % NSTAGE) * STAGE_BYTES,
+        dma_block<NW>(Bk, Cv, row0, i * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
                       sV + (i % NSTAGE) * STAGE_BYTES, w, lane);
     };
     issue(0);
@@ -420,19 +463,20 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     f32x16 Macc[TPW];
     {
         const float* st = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+        const float sg = anti ? -1.f : 1.f;
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
             const int t = t0 + u, a = t >> 2, b = t & 3;
             if (!transpose_state) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    Macc[u][v] = st[(32 * a + 8 * (v >> 2) + 4 * h + (v & 3)) * D + 32 * b + l32];
+                    Macc[u][v] = sg * st[(32 * a + 8 * (v >> 2) + 4 * h + (v & 3)) * D + 32 * b + l32];
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     f32x4 x = *reinterpret_cast<const f32x4*>(st + (32 * b + l32) * D + 32 * a + 8 * q + 4 * h);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) Macc[u][4 * q + e] = x[e];
+                    for (int e = 0; e < 4; ++e) Macc[u][4 * q + e] = sg * x[e];
                 }
             }
         }
@@ -453,24 +497,19 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             qf[ks] = __builtin_bit_cast(bf16x8, x);
         }
     };
-    load_q(reverse ? nch - 1 : 0);
+    load_q(0);
 
-    int bi = 0;          // index of the block being consumed, in walk order
-    for (int ci = 0; ci < nch; ++ci) {
-        const int c = reverse ? nch - 1 - ci : ci;
-        const int cn = reverse ? c - 1 : c + 1;          // next chunk in walk order
-        const int nblk = (c == nch - 1) ? nblk_tail : BPC;
-        const bool last_chunk = (ci + 1 == nch);
+    int bi = 0;          // index of the block being consumed
+    int prev_nblk = BPC;
+    for (int c = 0; c < nch; ++c) {
+        const int nblk = min(BPC, NB - c * BPC);
+        const bool last_chunk = (c + 1 == nch);
 
-#pragma unroll
-        for (int u = 0; u < TPW; ++u) {
-            const int t = t0 + u, a = t >> 2, b = t & 3;
-            const int row = 32 * b + l32;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                u32x2 pk = {pack2(Macc[u][4 * q], Macc[u][4 * q + 1]), pack2(Macc[u][4 * q + 2], Macc[u][4 * q + 3])};
-                *reinterpret_cast<u32x2*>(sM + tile_off(row, 4 * a + q) + 8 * h) = pk;
-            }
+        if (!anti) {
+            // The previous chunk read the snapshot in its first block; one of its later block
+            // barriers separates that from this write unless it had a single block.
+            if (prev_nblk < 2) __syncthreads();
+            write_snapshot<TPW>(sM, Macc, t0, l32, h, false);
         }
 
         f32x16 Oacc[4];
@@ -484,36 +523,20 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
             // this wave's loads of block bi have landed (those of bi+1 may still fly)
             if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
-            const int tok = tok_of(bi);
-            if (tok + KB > len) zero_tail_rows<NW>(tok, len, tK, tV, w, lane);
+            if (bi * KB + KB > len) zero_tail_rows<NW>(bi * KB, len, tK, tV, w, lane);
             __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
             if (bi + 2 < NB) issue(bi + 2);
+
+            if (!anti && jb == 0) inter_product<NOP>(Oacc, sM, qf, lo.nat);
 
             // Operand fetches are issued a batch ahead of the MFMAs that consume them (two
             // small register buffers); sched_barrier keeps the compiler from sinking the
             // reads back next to their uses.
             bf16x8 bufA[NOP], bufB[NOP];
-            if (jb == 0) {
-                // inter-chunk term: out^T += S^T A^T  with S^T = snapshot [d_v][d_k]
-                rd_inter<NOP>(bufA, sM, lo.nat[0]);
-                SCHED_FENCE();
-#pragma unroll
-                for (int ks = 0; ks < 8; ks += 2) {
-                    rd_inter<NOP>(bufB, sM, lo.nat[ks + 1]);
-                    SCHED_FENCE();
-                    mm_inter<NOP>(Oacc, bufA, qf[ks]);
-                    SCHED_FENCE();
-                    if (ks + 2 < 8) rd_inter<NOP>(bufA, sM, lo.nat[ks + 2]);
-                    SCHED_FENCE();
-                    mm_inter<NOP>(Oacc, bufB, qf[ks + 1]);
-                    SCHED_FENCE();
-                }
-            }
-
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int kt = 2 * jb + half;      // 32-key tile index inside the chunk
-                const bool active = reverse ? (kt >= rb) : (kt <= rb);
+                const bool active = anti ? (kt >= rb) : (kt <= rb);
                 if (!active) continue;
                 // scores^T (keys x queries) = Bk_tile A_w^T ; the Cv operands of the second
                 // product are fetched while the first one runs
@@ -543,7 +566,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = 8 * (v >> 2) + 4 * h + (v & 3);
-                        const bool keep = reverse ? (key >= l32) : (key <= l32);
+                        const bool keep = anti ? (key >= l32) : (key <= l32);
                         sc[v] = keep ? sc[v] : 0.f;
                     }
                 }
@@ -563,9 +586,10 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
                 SCHED_FENCE();
             }
 
-            // the rows of the next chunk replace qf while the state update and the store run
-            if (jb + 1 == nblk && !last_chunk) load_q(cn);
-            if (!last_chunk) {
+            // causal: the rows of the next chunk replace qf while the state update and the
+            // store run (anti-causal still needs qf for the inter product at the chunk's end)
+            if (!anti && jb + 1 == nblk && !last_chunk) load_q(c + 1);
+            if (anti || !last_chunk) {
                 // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
                 rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
                 SCHED_FENCE();
@@ -584,14 +608,23 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
                 mm_update<TPW, NOP>(Macc, bufB);
             }
         }
+        prev_nblk = nblk;
+
+        if (anti) {
+            // every wave read the previous snapshot before its previous store, and at least one
+            // block barrier has passed since
+            write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
+            __syncthreads();
+            inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            if (!last_chunk) load_q(c + 1);
+        }
 
         // Store this wave's 32 output rows.  The accumulators hold out^T (lane = row, four
         // consecutive d_v per register group); they are transposed through a wave-private
-        // 4 KiB piece of the snapshot area, half of d_v at a time, so that every lane stores
-        // 16 contiguous bytes and a wave instruction covers whole 128-byte line halves.
-        if (nblk < 2) __syncthreads();   // some wave may still read the snapshot in block 0
+        // 4 KiB LDS patch, half of d_v at a time, so that every lane stores 16 contiguous bytes
+        // and a wave instruction covers whole 128-byte line halves.
         {
-            char* stg = sM + w * 4096;
+            char* stg = sO + w * 4096;
             const int rbase = c * C + 32 * rb;
 #pragma unroll
             for (int hv = 0; hv < 2; ++hv) {
@@ -612,31 +645,31 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
                 }
             }
         }
-        if (!last_chunk) __syncthreads();   // staging reads done before the next snapshot write
     }
 }
 
 template <int C>
-hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1, int nprob,
-                         hipStream_t st)
+hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
+                         const AttnProblem& p2, int nprob, hipStream_t st)
 {
-    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB;   // 128 KiB
+    // stages + snapshot + 4 KiB of output staging per wave
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + (C / 32) * 4096;
     auto kern = attn_mfma_kernel<C>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    const unsigned gx = nprob == 2 ? 2u * (((unsigned)g.T_s + 7u) & ~7u) : (unsigned)g.T_s;
+    const unsigned gx = (unsigned)nprob * (((unsigned)g.T_s + 7u) & ~7u);
     dim3 grid(gx, g.G), block(C * 2);
-    hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, nprob);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, p2, nprob);
     return hipGetLastError();
 }
 
 AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const float* state, void* out,
-                         int transpose_state, int reverse)
+                         int transpose_state, int anti)
 {
     return AttnProblem{static_cast<const char*>(A), static_cast<const char*>(Bk),
                        static_cast<const char*>(Cv), state, static_cast<char*>(out), transpose_state,
-                       reverse};
+                       anti};
 }
 
 }  // namespace
@@ -658,25 +691,27 @@ hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float
     return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma(const Geom& g, const void* A, const void* Bk, const void* Cv,
-                            const float* state, void* out, int transpose_state, int reverse,
-                            hipStream_t st)
+hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                const float* P, void* O, hipStream_t st)
 {
-    const AttnProblem p = make_problem(A, Bk, Cv, state, out, transpose_state, reverse);
-    if (g.C == 256) return launch_attn_C<256>(g, p, p, 1, st);
-    return launch_attn_C<128>(g, p, p, 1, st);
+    const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
+    if (g.C == 256) return launch_attn_C<256>(g, p, p, p, 1, st);
+    return launch_attn_C<128>(g, p, p, p, 1, st);
 }
 
-hipError_t launch_attn_pair_mfma(const Geom& g, const void* A0, const void* A1, const void* X,
-                                 const void* Y, const float* state, void* out0, void* out1,
-                                 int reverse, hipStream_t st)
+hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                const void* dO, const float* P, const float* dR, void* dQ, void* dK,
+                                void* dV, hipStream_t st)
 {
-    // problem 0: (A0, Bk = X, Cv = Y), state as stored; problem 1: (A1, Bk = Y, Cv = X), whose
-    // state Y^T X is the transpose of the stored X^T Y.
-    const AttnProblem p0 = make_problem(A0, X, Y, state, out0, 0, reverse);
-    const AttnProblem p1 = make_problem(A1, Y, X, state, out1, 1, reverse);
-    if (g.C == 256) return launch_attn_C<256>(g, p0, p1, 2, st);
-    return launch_attn_C<128>(g, p0, p1, 2, st);
+    // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state V^T K is the
+    //     cached prefix read transposed.
+    // dV: anti-causal problem with (K, Q, dO); state = suffix of Q^T dO.
+    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = that suffix transposed.
+    const AttnProblem pq = make_problem(dO, V, K, P, dQ, 1, 0);
+    const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
+    const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
+    if (g.C == 256) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
+    return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }
 
 }  // namespace lasp2

@@ -79,15 +79,6 @@ hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, fl
     return launch_states_generic(g, dtype, K, V, M, st);
 }
 
-hipError_t run_attn(const Geom& g, int dtype, const void* A, const void* Bk, const void* Cv,
-                    const float* state, void* out, int transpose_state, int reverse,
-                    hipStream_t st)
-{
-    if (mfma_path_supported(g, dtype))
-        return launch_attn_mfma(g, A, Bk, Cv, state, out, transpose_state, reverse, st);
-    return launch_attn_generic(g, dtype, A, Bk, Cv, state, out, transpose_state, reverse, st);
-}
-
 }  // namespace
 }  // namespace lasp2
 
@@ -140,7 +131,7 @@ int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P, int r
     if (empty) return LASP2_OK;
     rc = check_ptrs({M, P});
     if (rc != LASP2_OK) return rc;
-    return from_hip(launch_state_prefix(g, M, P, reverse ? 1 : 0, (hipStream_t)stream));
+    return from_hip(launch_state_prefix(g, M, P, reverse ? 1 : 0, 0, (hipStream_t)stream));
 }
 
 int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
@@ -153,7 +144,9 @@ int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     if (empty) return LASP2_OK;
     rc = check_ptrs({Q, K, V, P, O});
     if (rc != LASP2_OK) return rc;
-    return from_hip(run_attn(g, desc->dtype, Q, K, V, P, O, 0, 0, (hipStream_t)stream));
+    hipStream_t st = (hipStream_t)stream;
+    if (mfma_path_supported(g, desc->dtype)) return from_hip(launch_attn_fwd_mfma(g, Q, K, V, P, O, st));
+    return from_hip(launch_attn_generic(g, desc->dtype, Q, K, V, P, O, 0, 0, st));
 }
 
 int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
@@ -171,24 +164,25 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     if (workspace_bytes < need) return LASP2_ERR_WORKSPACE;
 
     hipStream_t st = (hipStream_t)stream;
-    float* dP = static_cast<float*>(workspace);
-    // dM_t = Q_t^T dO_t per slot, then its suffix combine in place.
-    hipError_t e = run_states(g, desc->dtype, Q, dO, dP, st);
+    float* dR = static_cast<float*>(workspace);
+    const bool fast = mfma_path_supported(g, desc->dtype);
+    // dM_t = Q_t^T dO_t per slot, then its suffix combine in place: exclusive for the plain
+    // kernels (which walk each slot backwards), inclusive for the MFMA kernels (which walk
+    // forwards and subtract, see attn_mfma_kernel).
+    hipError_t e = run_states(g, desc->dtype, Q, dO, dR, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    e = launch_state_prefix(g, dP, dP, 1, st);
+    e = launch_state_prefix(g, dR, dR, 1, fast ? 1 : 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    if (fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
     // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
-    e = run_attn(g, desc->dtype, dO, V, K, P, dQ, 1, 0, st);
+    e = launch_attn_generic(g, desc->dtype, dO, V, K, P, dQ, 1, 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     // dV: anti-causal problem with (K, Q, dO); state dM_{t+1:T} = sum Q^T dO.
-    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
-    // Both stream Q and dO; the MFMA path runs them as one paired launch.
-    if (mfma_path_supported(g, desc->dtype))
-        return from_hip(launch_attn_pair_mfma(g, K, V, Q, dO, dP, dV, dK, 1, st));
-    e = run_attn(g, desc->dtype, K, Q, dO, dP, dV, 0, 1, st);
+    e = launch_attn_generic(g, desc->dtype, K, Q, dO, dR, dV, 0, 1, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    e = run_attn(g, desc->dtype, V, dO, Q, dP, dK, 1, 1, st);
+    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
+    e = launch_attn_generic(g, desc->dtype, V, dO, Q, dR, dK, 1, 1, st);
     return from_hip(e);
 }
 

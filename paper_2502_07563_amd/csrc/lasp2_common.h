@@ -63,20 +63,21 @@ hipError_t launch_states_generic(const Geom& g, int dtype, const void* K, const 
 hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const void* Bk,
                                const void* Cv, const float* state, void* out,
                                int transpose_state, int reverse, hipStream_t st);
-hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse,
+// inclusive = 0: P[s] excludes M[s] (the public entry point); 1: P[s] includes it.
+hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, int inclusive,
                                hipStream_t st);
 
 // bf16 MFMA kernels (d = 128, C in {128,256}).
 bool mfma_path_supported(const Geom& g, int dtype);
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
                               hipStream_t st);
-hipError_t launch_attn_mfma(const Geom& g, const void* A, const void* Bk, const void* Cv,
-                            const float* state, void* out, int transpose_state, int reverse,
-                            hipStream_t st);
-// Two problems that stream the same tensors X, Y with swapped roles, in one launch:
-//   out0 = attn(A0, Bk = X, Cv = Y, state),  out1 = attn(A1, Bk = Y, Cv = X, state^T).
-hipError_t launch_attn_pair_mfma(const Geom& g, const void* A0, const void* A1, const void* X,
-                                 const void* Y, const float* state, void* out0, void* out1,
-                                 int reverse, hipStream_t st);
+// O = fused intra + inter pass with prefix states P.
+hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                const float* P, void* O, hipStream_t st);
+// dQ, dV, dK in one launch.  P: exclusive prefix states of K^T V (from the forward);
+// dR: INCLUSIVE suffix states of Q^T dO (slot s holds the sum over slots >= s of its document).
+hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                const void* dO, const float* P, const float* dR, void* dQ, void* dK,
+                                void* dV, hipStream_t st);
 
 }  // namespace lasp2

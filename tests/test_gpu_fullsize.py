@@ -31,7 +31,10 @@ def _run_config(name):
     bd.lasp2_state_prefix(p, M, P, False)
     O = torch.empty_like(dev["Q"])
     bd.lasp2_attn_fwd(p, dev["Q"], dev["K"], dev["V"], P, O)
-    dQ, dK, dV, dP = bd.backward(p, dev["Q"], dev["K"], dev["V"], dev["dO"], P)
+    dQ, dK, dV, _ = bd.backward(p, dev["Q"], dev["K"], dev["V"], dev["dO"], P)
+    dP = torch.empty_like(M)
+    bd.lasp2_chunk_states(p, dev["Q"], dev["dO"], dP)
+    bd.lasp2_state_prefix(p, dP, dP, True)
     torch.cuda.synchronize()
     out = dict(O=O, dQ=dQ, dK=dK, dV=dV, M=M, P=P, dP=dP)
     return cfg, cu, out

@@ -46,8 +46,13 @@ def _run_all(oracle, B, H, N, d, C, L, dtype, seed, cu=None, check_bwd=True):
         bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
         torch.cuda.synchronize()
         dQ_ref, dK_ref, dV_ref = oracle.bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu)
+        # dM_t = Q_t^T dO_t and its suffix combine through the public entry points
+        dP = torch.empty_like(M)
+        bd.lasp2_chunk_states(p, Q, dO, dP)
+        bd.lasp2_state_prefix(p, dP, dP, True)
+        torch.cuda.synchronize()
         dP_ref = oracle.state_prefix(oracle.chunk_states(x64["Q"], x64["dO"], bounds), first, reverse=True)
-        errs["dP"] = rel_l2(to_host(ws), dP_ref)
+        errs["dP"] = rel_l2(to_host(dP), dP_ref)
         errs["dQ"] = rel_l2(to_host(dQ), dQ_ref)
         errs["dK"] = rel_l2(to_host(dK), dK_ref)
         errs["dV"] = rel_l2(to_host(dV), dV_ref)
