@@ -7,9 +7,10 @@ that is already resident in HBM.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
 
 Prints ONE JSON line.  `value` is tokens/s for the layer; `roofline` prices the
-dominant kernel (the fused attention pass) against HBM peak using its algorithmic
-bytes and its HIP-event duration measured inside the timed loop; `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the same workload.
+dominant kernel (the fused attention pass, launched once by the forward and once by
+the backward) against HBM peak using its algorithmic bytes and its HIP-event duration
+measured inside the timed loop; `cpu_baseline` is the CPU oracle timed on a bounded
+sample of the same workload.
 """
 import argparse
 import json
@@ -23,6 +24,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+# HBM bytes per launch of the attention kernel (average of its forward and backward launch),
+# from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/lasp2_kernels_cfg3_hbm_traffic.txt (counters cannot be read from inside this script).
+MEASURED_TRAFFIC_BYTES = {"cfg3": 6.302e9}
 
 
 def nominal_flops_per_token_head(d, C):
@@ -132,11 +138,23 @@ def main():
     seg = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]
 
     esz = 2 if dtype == "bf16" else 4
-    # fused attention pass, one launch: reads A, Bk, Cv and the slot states, writes out
-    attn_bytes = 4 * B * H * N * d * esz + B * H * T_s * d * d * 4
-    attn_ms = seg[2]
-    achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+    # Dominant kernel: the fused attention pass, launched twice per step.  Algorithmic bytes:
+    #   forward launch : Q, K, V read, O written, one state array read            (4 passes)
+    #   backward launch: Q, K, V, dO read once, dQ, dK, dV written, P read once and the suffix
+    #                    states twice (dV and dK each read them)                   (7 passes)
+    tensor = B * H * N * d * esz
+    states = B * H * T_s * d * d * 4
+    bytes_fwd = 4 * tensor + states
+    bytes_bwd = 7 * tensor + 3 * states
+    # HIP events bracket the forward launch exactly.  The backward launch sits inside
+    # lasp2_attn_bwd behind a states kernel and a prefix kernel that are the same launches as
+    # the step's chunk_states / state_prefix segments, so its time is attn_bwd minus those two.
+    t_fwd = seg[2]
+    t_bwd = seg[3] - seg[0] - seg[1]
+    avg_ms = 0.5 * (t_fwd + t_bwd)
+    achieved = 0.5 * (bytes_fwd + bytes_bwd) / (avg_ms * 1e-3) / 1e9
     flops_nominal = nominal_flops_per_token_head(d, C) * tokens * H
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
     out = {
         "metric": "fwd+bwd tokens/s per layer",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -147,9 +165,11 @@ def main():
                    "state_slots": int(T_s)},
         "ms": {"chunk_states": seg[0], "state_prefix": seg[1], "attn_fwd": seg[2], "attn_bwd": seg[3]},
         "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
-        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel (as launched by lasp2_attn_fwd)",
+        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel<256>, average of its two launches per step",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "avg_launch_ms": avg_ms, "fwd_launch_ms": t_fwd, "bwd_launch_ms": t_bwd,
+                     "fwd_launch_GBps": bytes_fwd / (t_fwd * 1e-3) / 1e9},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
