@@ -138,3 +138,29 @@ def test_result_does_not_depend_on_C_or_L(oracle):
         else:
             for a, b in zip(got, ref):
                 assert rel_l2(a, b) <= TOL["bf16"]
+
+
+def test_runs_on_the_callers_stream(oracle):
+    """Work is enqueued on the stream handed in: results on a side stream match the default stream."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    p = bd.Problem(1, 2, 2048, 128, 256, 512, "bf16")
+    x = host_inputs(70, 2, 2048, 128, "bf16")
+    Q, K, V, dO = (to_device(x[n], 1, 2, "bf16") for n in ("Q", "K", "V", "dO"))
+    O0, P0 = bd.forward(p, Q, K, V)
+    g0 = bd.backward(p, Q, K, V, dO, P0)[:3]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        O1, P1 = bd.forward(p, Q, K, V, stream=side)
+        g1 = bd.backward(p, Q, K, V, dO, P1, stream=side)[:3]
+    side.synchronize()
+    assert torch.equal(O0, O1) and torch.equal(P0, P1)
+    for a, b in zip(g0, g1):
+        assert torch.equal(a, b)
+
+
+def test_many_slots_not_multiple_of_eight(oracle):
+    """Slot counts that do not fill the last group of eight workgroups of a launch."""
+    _run_all(oracle, 1, 1, 256 * 11 + 70, 128, 256, 256, "bf16", seed=71)
+    _run_all(oracle, 2, 1, 256 * 3, 128, 256, 256, "bf16", seed=72)
