@@ -193,3 +193,77 @@ def backward_by_algorithm(Q, K, V, dO, bounds, first=None):
     dM = chunk_states(Q, dO, bounds)
     dP = state_prefix(dM, first, reverse=True)
     return attn_bwd_chunked(Q, K, V, dO, P, dP, bounds) + (dM, dP)
+
+
+# ---------------------------------------------------------------------------
+# Without masking (Algorithm "LASP-2 w/o Masking" and its backward pass)
+# ---------------------------------------------------------------------------
+
+def nomask_fwd_def(Q, K, V, cu=None):
+    """O_i = sum over ALL j of the document of (q_i . k_j) v_j, brute force."""
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    O = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_nomask_fwd_def(q, k, v, O.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                       ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1))
+    return O
+
+
+def nomask_bwd_def(Q, K, V, dO, cu=None):
+    """Analytic gradient of <dO, O> for the unmasked definition, brute force."""
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO)
+    dQ = np.empty((G, N, d)); dK = np.empty((G, N, d)); dV = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_nomask_bwd_def(q, k, v, g, dQ.ctypes.data_as(_c_dp), dK.ctypes.data_as(_c_dp),
+                                       dV.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                       ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1))
+    return dQ, dK, dV
+
+
+def state_total(M, first=None):
+    """Sum of the [G, T, d, d] states of each document, handed to every chunk of that document."""
+    G, T, d, d2 = M.shape
+    assert d == d2
+    M, m = _d(M)
+    S = np.empty_like(M)
+    if first is None:
+        fp = None
+    else:
+        first = np.ascontiguousarray(first, dtype=np.int32)
+        assert first.shape == (T,)
+        fp = first.ctypes.data_as(_c_ip)
+    _lib().lasp2_oracle_state_total(m, S.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(T),
+                                    ctypes.c_long(d), fp)
+    return S
+
+
+def rows_times_state(A, S, bounds, transpose=False):
+    """out_t = A_t S_t (or A_t S_t^T) per chunk."""
+    G, N, d = _gnd(A)
+    A, a = _d(A); S, s = _d(S)
+    b, bp = _l(_bounds(bounds, N))
+    assert S.shape == (G, len(b) - 1, d, d)
+    out = np.zeros((G, N, d))
+    _lib().lasp2_oracle_rows_times_state(a, s, out.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                         ctypes.c_long(d), bp, ctypes.c_long(len(b) - 1),
+                                         ctypes.c_int(1 if transpose else 0))
+    return out
+
+
+def nomask_forward_by_algorithm(Q, K, V, bounds, first=None):
+    """Forward steps without masking: M_t -> M_{1:T} -> O_t = Q_t M_{1:T}."""
+    M = chunk_states(K, V, bounds)
+    S = state_total(M, first)
+    return rows_times_state(Q, S, bounds), M, S
+
+
+def nomask_backward_by_algorithm(Q, K, V, dO, bounds, first=None):
+    """Backward steps without masking: dM_t -> dM_{1:T}; dQ = dO M^T, dK = V dM^T, dV = K dM."""
+    S = state_total(chunk_states(K, V, bounds), first)
+    dS = state_total(chunk_states(Q, dO, bounds), first)
+    dQ = rows_times_state(dO, S, bounds, transpose=True)
+    dK = rows_times_state(V, dS, bounds, transpose=True)
+    dV = rows_times_state(K, dS, bounds)
+    return dQ, dK, dV, dS

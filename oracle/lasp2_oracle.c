@@ -28,6 +28,10 @@
  *               the steps of Algorithm "LASP-2 w/ Masking" and its backward,
  *               in the paper's order, over an arbitrary partition of the
  *               tokens into chunks.
+ *   nomask_*_def / state_total / rows_times_state :
+ *               linear attention without the mask (every token of a document
+ *               attends to every token of it): the double-sum definition and
+ *               the steps of Algorithm "LASP-2 w/o Masking" and its backward.
  *
  * Readings of the paper used here:
  *   - the mask Psi multiplies elementwise, so the entries the paper prints as
@@ -420,6 +424,121 @@ void lasp2_oracle_attn_bwd_chunked(const double* Q, const double* K, const doubl
             }
             free(S);
             free(Gm);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Without masking.  Definition: O[i,:] = sum_{j: doc(j)=doc(i)} (q_i.k_j) v_j */
+/* (Section "LASP-2 without Masking": O = (Q K^T) V with no mask).      */
+/* ------------------------------------------------------------------ */
+void lasp2_oracle_nomask_fwd_def(const double* Q, const double* K, const double* V,
+                                 double* O, long G, long N, long d,
+                                 const long* cu, long n_docs)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            double* o = O + (g * N + i) * d;
+            for (long b = 0; b < d; ++b) o[b] = 0.0;
+            for (long j = cu[doc[i]]; j < cu[doc[i] + 1]; ++j) {
+                double s = dot(Q + (g * N + i) * d, K + (g * N + j) * d, d);
+                const double* v = V + (g * N + j) * d;
+                for (long b = 0; b < d; ++b) o[b] += s * v[b];
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Gradient of <dO, O> for the unmasked definition.  With S_ij = q_i.k_j and
+ * G_ij = dO_i.v_j over all pairs of one document:
+ *   dQ[i,:] = sum_j G_ij k_j,   dK[j,:] = sum_i G_ij q_i,   dV[j,:] = sum_i S_ij dO_i.
+ */
+void lasp2_oracle_nomask_bwd_def(const double* Q, const double* K, const double* V,
+                                 const double* dO, double* dQ, double* dK, double* dV,
+                                 long G, long N, long d, const long* cu, long n_docs)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            long lo = cu[doc[i]], hi = cu[doc[i] + 1];
+            double* dq = dQ + (g * N + i) * d;
+            double* dk = dK + (g * N + i) * d;
+            double* dv = dV + (g * N + i) * d;
+            for (long a = 0; a < d; ++a) { dq[a] = 0.0; dk[a] = 0.0; dv[a] = 0.0; }
+            for (long j = lo; j < hi; ++j) {
+                /* row i as a query against key/value j */
+                double gij = dot(dO + (g * N + i) * d, V + (g * N + j) * d, d);
+                const double* kj = K + (g * N + j) * d;
+                for (long a = 0; a < d; ++a) dq[a] += gij * kj[a];
+                /* row i as a key/value against query j */
+                double gji = dot(dO + (g * N + j) * d, V + (g * N + i) * d, d);
+                double sji = dot(Q + (g * N + j) * d, K + (g * N + i) * d, d);
+                const double* qj = Q + (g * N + j) * d;
+                const double* doj = dO + (g * N + j) * d;
+                for (long a = 0; a < d; ++a) { dk[a] += gji * qj[a]; dv[a] += sji * doj[a]; }
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Line "Compute M_{1:T} = Sum([M_t]_1^T)" of Algorithm "LASP-2 w/o Masking",
+ * by the recursive accumulation the text describes (M_{1:t-1} + M_t), once per
+ * document; every chunk t receives the total of its own document, as every
+ * rank holds M_{1:T} after the gather.  first as in state_prefix.
+ */
+void lasp2_oracle_state_total(const double* M, double* S, long G, long n_chunks,
+                              long d, const int* first)
+{
+    long dd = d * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* run = (double*)malloc(sizeof(double) * (size_t)dd);
+        long t0 = 0;
+        while (t0 < n_chunks) {
+            long t1 = t0 + 1;
+            while (t1 < n_chunks && !(first && first[t1])) ++t1;
+            memset(run, 0, sizeof(double) * (size_t)dd);
+            for (long t = t0; t < t1; ++t) {
+                const double* m = M + (g * n_chunks + t) * dd;
+                for (long e = 0; e < dd; ++e) run[e] += m[e];
+            }
+            for (long t = t0; t < t1; ++t) memcpy(S + (g * n_chunks + t) * dd, run, sizeof(double) * (size_t)dd);
+            t0 = t1;
+        }
+        free(run);
+    }
+}
+
+/*
+ * out_t = A_t S_t (transpose == 0) or A_t S_t^T (transpose != 0) for every
+ * chunk t: the lines O_t = Q_t M_{1:T}, dQ_t = dO_t M_{1:T}^T,
+ * dK_t = V_t dM_{1:T}^T and dV_t = K_t dM_{1:T} of the two algorithms
+ * without masking.  S is [G][n_chunks][d][d].
+ */
+void lasp2_oracle_rows_times_state(const double* A, const double* S, double* out,
+                                   long G, long N, long d, const long* bounds,
+                                   long n_chunks, int transpose)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            const double* s = S + (g * n_chunks + t) * d * d;
+            for (long i = bounds[t]; i < bounds[t + 1]; ++i) {
+                const double* a = A + (g * N + i) * d;
+                double* o = out + (g * N + i) * d;
+                for (long c = 0; c < d; ++c) {
+                    double acc = 0.0;
+                    for (long r = 0; r < d; ++r) acc += a[r] * (transpose ? s[c * d + r] : s[r * d + c]);
+                    o[c] = acc;
+                }
+            }
         }
     }
 }
