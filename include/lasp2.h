@@ -1,7 +1,8 @@
 /*
  * lasp2.h - C ABI of the single-GPU hot path of LASP-2 with masking:
  * chunked causal (unnormalised, identity-kernel) linear attention, forward and
- * backward, for AMD MI355X (gfx950).
+ * backward, for AMD MI355X (gfx950); and, at the end, of LASP-2 without
+ * masking.
  *
  * Problem statement (LASP-2 paper, Sec. "Preliminary", Eq. (3); Sec. "LASP-2
  * with Masking", Algorithm "LASP-2 w/ Masking"; appendix Algorithm "LASP-2 w/
@@ -89,7 +90,7 @@ typedef struct lasp2_desc {
 /* Number of state slots T_s per (b,h) for this descriptor (see "Slots" above). */
 int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s);
 
-/* Bytes of device scratch lasp2_attn_bwd needs: one fp32 state array
+/* Bytes of device scratch lasp2_attn_bwd and lasp2_nomask_bwd need: one fp32 state array
  * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine. */
 int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
 
@@ -139,6 +140,48 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                    const void* V, const void* dO, const float* P,
                    void* dQ, void* dK, void* dV,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Without masking (LASP-2 paper, Sec. "LASP-2 without Masking", Algorithm
+ * "LASP-2 w/o Masking" and appendix Algorithm "LASP-2 w/o Masking (Backward
+ * Pass)") ----
+ * Every token attends to every token of its sequence (document):
+ *     O = (Q K^T) V = Q (K^T V),
+ * so the states are summed instead of prefix-combined and each slot needs one
+ * product with the total.  The slot states come from lasp2_chunk_states; C
+ * plays no part here beyond fixing the slots through L.
+ */
+
+/*
+ * Line "M_{1:T} = Sum([M_t])" of the algorithm, standing in for AllGather +
+ * Sum: S[s] = sum of M[r] over all slots r of the document that owns slot s,
+ * so that every slot holds its document's total (as every rank does after the
+ * gather).  In: M [B,H,T_s,d,d] fp32.  Out: S, same shape; S may alias M
+ * exactly (in place); partial overlap is not allowed.  The forward's S is the
+ * array the paper caches in HBM for the backward.
+ */
+int lasp2_state_total(const lasp2_desc_t* desc, const float* M, float* S, void* stream);
+
+/*
+ * Line "O_t = Q_t M_{1:T}".  In: Q [B,H,N,d]; S [B,H,T_s,d,d] fp32 from
+ * lasp2_state_total.  Out: O [B,H,N,d] in `dtype`, written once.
+ */
+int lasp2_nomask_fwd(const lasp2_desc_t* desc, const void* Q, const float* S, void* O,
+                     void* stream);
+
+/*
+ * Backward without masking: dM_t = Q_t^T dO_t per slot and its total dM_{1:T}
+ * (both into `workspace`; the range printed in the algorithm's Sum line is
+ * read as the sum over all chunks), then
+ *   dQ_t = dO_t M_{1:T}^T,   dK_t = V_t dM_{1:T}^T,   dV_t = K_t dM_{1:T}.
+ * In: Q,K,V,dO [B,H,N,d]; S = the forward's cached totals.  Out: dQ,dK,dV
+ * [B,H,N,d].  `workspace`: device scratch of at least lasp2_workspace_size()
+ * bytes, 16-byte aligned; on return it holds dM_{1:T} in every slot.
+ */
+int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
+                     const void* V, const void* dO, const float* S,
+                     void* dQ, void* dK, void* dV,
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Static, human-readable text for a status code (never NULL). */
 const char* lasp2_status_string(int status);

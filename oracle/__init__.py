@@ -222,6 +222,24 @@ def nomask_bwd_def(Q, K, V, dO, cu=None):
     return dQ, dK, dV
 
 
+def nomask_def_rows(Q, K, V, dO, rows, which, cu=None):
+    """Rows `rows` of O (which=0), dQ (1), dK (2) or dV (3) of the unmasked definition, ONE group."""
+    N, d = Q.shape
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    if dO is None:
+        assert which == 0
+        g = None
+    else:
+        dO, g = _d(dO)
+    rows, r = _l(rows)
+    out = np.empty((len(rows), d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_nomask_def_rows(q, k, v, g, ctypes.c_long(N), ctypes.c_long(d), c,
+                                        ctypes.c_long(len(cu) - 1), r, ctypes.c_long(len(rows)),
+                                        ctypes.c_int(which), out.ctypes.data_as(_c_dp))
+    return out
+
+
 def state_total(M, first=None):
     """Sum of the [G, T, d, d] states of each document, handed to every chunk of that document."""
     G, T, d, d2 = M.shape

@@ -542,3 +542,39 @@ void lasp2_oracle_rows_times_state(const double* A, const double* S, double* out
         }
     }
 }
+
+/*
+ * Selected rows of the unmasked definition (one group; Q,K,V,dO are [N][d]).
+ * which: 0 -> O rows, 1 -> dQ rows, 2 -> dK rows, 3 -> dV rows; dO may be NULL
+ * for which == 0.
+ */
+void lasp2_oracle_nomask_def_rows(const double* Q, const double* K, const double* V,
+                                  const double* dO, long N, long d, const long* cu,
+                                  long n_docs, const long* rows, long n_rows, int which,
+                                  double* out)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < n_rows; ++r) {
+        long i = rows[r];
+        long lo = cu[doc[i]], hi = cu[doc[i] + 1];
+        double* o = out + r * d;
+        for (long a = 0; a < d; ++a) o[a] = 0.0;
+        for (long j = lo; j < hi; ++j) {
+            if (which == 0) {            /* O_i   = sum_j (q_i.k_j) v_j   */
+                double s = dot(Q + i * d, K + j * d, d);
+                for (long a = 0; a < d; ++a) o[a] += s * V[j * d + a];
+            } else if (which == 1) {     /* dQ_i  = sum_j (dO_i.v_j) k_j  */
+                double gij = dot(dO + i * d, V + j * d, d);
+                for (long a = 0; a < d; ++a) o[a] += gij * K[j * d + a];
+            } else if (which == 2) {     /* dK_i  = sum_j (dO_j.v_i) q_j  */
+                double gji = dot(dO + j * d, V + i * d, d);
+                for (long a = 0; a < d; ++a) o[a] += gji * Q[j * d + a];
+            } else {                     /* dV_i  = sum_j (q_j.k_i) dO_j  */
+                double sji = dot(Q + j * d, K + i * d, d);
+                for (long a = 0; a < d; ++a) o[a] += sji * dO[j * d + a];
+            }
+        }
+    }
+    free(doc);
+}

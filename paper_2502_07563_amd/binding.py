@@ -53,10 +53,14 @@ def lib():
         L.lasp2_state_prefix.argtypes = [dp, vp, vp, ctypes.c_int, vp]
         L.lasp2_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.lasp2_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.lasp2_state_total.argtypes = [dp, vp, vp, vp]
+        L.lasp2_nomask_fwd.argtypes = [dp, vp, vp, vp, vp]
+        L.lasp2_nomask_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.lasp2_status_string.argtypes = [ctypes.c_int]
         L.lasp2_status_string.restype = ctypes.c_char_p
         for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
-                     "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd"):
+                     "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_state_total",
+                     "lasp2_nomask_fwd", "lasp2_nomask_bwd"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -138,6 +142,21 @@ def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=Non
                                 _stream(stream)), "lasp2_attn_bwd")
 
 
+def lasp2_state_total(p: Problem, M, S, stream=None):
+    _check(lib().lasp2_state_total(p.ref, _ptr(M), _ptr(S), _stream(stream)), "lasp2_state_total")
+
+
+def lasp2_nomask_fwd(p: Problem, Q, S, O, stream=None):
+    _check(lib().lasp2_nomask_fwd(p.ref, _ptr(Q), _ptr(S), _ptr(O), _stream(stream)), "lasp2_nomask_fwd")
+
+
+def lasp2_nomask_bwd(p: Problem, Q, K, V, dO, S, dQ, dK, dV, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lasp2_nomask_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(S), _ptr(dQ),
+                                  _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
+                                  _stream(stream)), "lasp2_nomask_bwd")
+
+
 def alloc_states(p: Problem, device="cuda"):
     """fp32 [B,H,T_s,d,d] state array (device memory from torch)."""
     return torch.empty((p.B, p.H, lasp2_num_slots(p), p.d, p.d), dtype=torch.float32, device=device)
@@ -158,4 +177,22 @@ def backward(p: Problem, Q, K, V, dO, P, stream=None):
     ws = alloc_states(p, Q.device)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws, stream)
+    return dQ, dK, dV, ws
+
+
+def nomask_forward(p: Problem, Q, K, V, stream=None):
+    """chunk_states -> state_total (in place) -> nomask_fwd.  Returns (O, S)."""
+    S = alloc_states(p, Q.device)
+    O = torch.empty_like(Q)
+    lasp2_chunk_states(p, K, V, S, stream)
+    lasp2_state_total(p, S, S, stream)
+    lasp2_nomask_fwd(p, Q, S, O, stream)
+    return O, S
+
+
+def nomask_backward(p: Problem, Q, K, V, dO, S, stream=None):
+    """nomask_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, workspace)."""
+    ws = alloc_states(p, Q.device)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    lasp2_nomask_bwd(p, Q, K, V, dO, S, dQ, dK, dV, ws, stream)
     return dQ, dK, dV, ws

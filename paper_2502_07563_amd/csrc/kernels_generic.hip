@@ -198,6 +198,107 @@ __global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const fl
     }
 }
 
+// S[s] = sum of M over all slots of the document that owns slot s (the state every rank holds
+// after the gather and the sum when there is no mask).  Each thread owns four elements of the
+// d x d state and sums the document's slots in ascending order before it writes any of them,
+// so S may alias M.
+__global__ __launch_bounds__(kThreads) void state_total_kernel(Geom g, const float* M, float* S)
+{
+    const int dd = g.d * g.d;
+    const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (e >= dd) return;
+    const size_t base = (size_t)blockIdx.y * (size_t)g.T_s * dd + e;
+    const int ndocs = g.n_seqs ? g.n_seqs : 1;
+    int s0 = 0;
+    for (int k = 0; k < ndocs; ++k) {
+        const int dlen = g.n_seqs ? (g.cu[k + 1] - g.cu[k]) : g.N;
+        const int ns = (int)(((int64_t)dlen + g.L - 1) / g.L);
+        float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int r = 0; r < ns; ++r) {
+            const float4 m = *reinterpret_cast<const float4*>(M + base + (size_t)(s0 + r) * dd);
+            run.x += m.x; run.y += m.y; run.z += m.z; run.w += m.w;
+        }
+        for (int r = 0; r < ns; ++r) *reinterpret_cast<float4*>(S + base + (size_t)(s0 + r) * dd) = run;
+        s0 += ns;
+    }
+}
+
+// out = A * state (or A * state^T) for the rows of one slot.  The state sits in LDS as
+// sS[r][c] = the factor of A[.,r] in out[.,c]; thread (rg, c) produces column c of the rows
+// rg, rg + NRG, ... of each tile of kProjRows * NRG rows.
+constexpr int kProjRows = 8;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void rows_state_generic_kernel(Geom g, const T* __restrict__ A,
+                                                                      const float* __restrict__ state,
+                                                                      T* __restrict__ out, int transpose)
+{
+    constexpr int NRG = kThreads / D, RT = kProjRows * NRG;
+    extern __shared__ float smem_f[];
+    float* sS = smem_f;            // [D][D]
+    float* sA = smem_f + D * D;    // [RT][D]
+    const int s = blockIdx.x, grp = blockIdx.y;
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    if (len <= 0) return;
+    const float* st_ = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+    for (int i = threadIdx.x; i < D * D; i += kThreads) {
+        const int r = i / D, c = i % D;
+        sS[i] = transpose ? st_[c * D + r] : st_[i];
+    }
+    const int c = threadIdx.x % D, rg = threadIdx.x / D;
+    const size_t gbase = ((size_t)grp * (size_t)g.N + tok0) * D;
+    for (int r0 = 0; r0 < len; r0 += RT) {
+        __syncthreads();   // state staged / previous tile consumed
+        for (int i = threadIdx.x; i < RT * D; i += kThreads) {
+            const int row = r0 + i / D;
+            sA[i] = row < len ? ld(A + gbase + (size_t)row * D + i % D) : 0.f;
+        }
+        __syncthreads();
+        float acc[kProjRows];
+#pragma unroll
+        for (int j = 0; j < kProjRows; ++j) acc[j] = 0.f;
+        for (int r = 0; r < D; ++r) {
+            const float w = sS[r * D + c];
+#pragma unroll
+            for (int j = 0; j < kProjRows; ++j) acc[j] = fmaf(sA[(rg + j * NRG) * D + r], w, acc[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kProjRows; ++j) {
+            const int row = r0 + rg + j * NRG;
+            if (row < len) st(out + gbase + (size_t)row * D + c, acc[j]);
+        }
+    }
+}
+
+template <typename T, int D>
+hipError_t rows_state_generic_TD(const Geom& g, const T* A, const float* state, T* out, int tr,
+                                 hipStream_t st)
+{
+    constexpr size_t smem = sizeof(float) * ((size_t)D * D + (size_t)kProjRows * (kThreads / D) * D);
+    auto kern = rows_state_generic_kernel<T, D>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(g.T_s, g.G), block(kThreads);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, A, state, out, tr);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t rows_state_generic_T(const Geom& g, const T* A, const float* state, T* out, int tr,
+                                hipStream_t st)
+{
+    switch (g.d) {
+        case 16: return rows_state_generic_TD<T, 16>(g, A, state, out, tr, st);
+        case 32: return rows_state_generic_TD<T, 32>(g, A, state, out, tr, st);
+        case 64: return rows_state_generic_TD<T, 64>(g, A, state, out, tr, st);
+        default: return rows_state_generic_TD<T, 128>(g, A, state, out, tr, st);
+    }
+}
+
 template <typename T>
 hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, hipStream_t st)
 {
@@ -262,6 +363,24 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const vo
                           static_cast<const __hip_bfloat16*>(Bk),
                           static_cast<const __hip_bfloat16*>(Cv), state,
                           static_cast<__hip_bfloat16*>(out), transpose_state, reverse, st);
+}
+
+hipError_t launch_state_total(const Geom& g, const float* M, float* S, hipStream_t st)
+{
+    const int dd = g.d * g.d;
+    dim3 grid((dd / 4 + kThreads - 1) / kThreads, g.G), block(kThreads);
+    hipLaunchKernelGGL(state_total_kernel, grid, block, 0, st, g, M, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_state_generic(const Geom& g, int dtype, const void* A, const float* state,
+                                     void* out, int transpose_state, hipStream_t st)
+{
+    if (dtype == LASP2_F32)
+        return rows_state_generic_T(g, static_cast<const float*>(A), state, static_cast<float*>(out),
+                                    transpose_state, st);
+    return rows_state_generic_T(g, static_cast<const __hip_bfloat16*>(A), state,
+                                static_cast<__hip_bfloat16*>(out), transpose_state, st);
 }
 
 hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, int inclusive,

@@ -672,6 +672,145 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
                        anti};
 }
 
+// =====================================================================================
+// Rows times a slot state, for the path without masking: out = A W over the rows of one slot,
+// W = state[slot] or its transpose (O_t = Q_t M_{1:T}; dQ_t = dO_t M_{1:T}^T, dK_t = V_t
+// dM_{1:T}^T, dV_t = K_t dM_{1:T}).  The work is two passes over HBM per product (rows in,
+// rows out), so the kernel only has to keep loads in flight: eight waves, each fetching its
+// next 32 rows while the matrix cores handle the current ones.  W sits in LDS as bf16,
+// [column of out][contracted index], the layout the inter-chunk product of the fused pass uses.
+// =====================================================================================
+constexpr int RS_NW = 8;
+
+struct RowsStateArgs {
+    const char* A;
+    const float* state;
+    char* out;
+    int transpose_state;
+};
+
+__global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, RowsStateArgs p0, RowsStateArgs p1,
+                                                                     RowsStateArgs p2, int nprob)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sW = smem;               // bf16 [128 columns of out][128 contracted], swizzled tile
+    char* sO = smem + D * ROWB;    // output staging, 4 KiB per wave
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int h = lane >> 5, l32 = lane & 31;
+    // same workgroup-to-slot mapping as the fused pass: the nprob products of a slot share an XCD
+    const int s = (int)(blockIdx.x / (8u * nprob)) * 8 + (int)(blockIdx.x & 7u);
+    const int prob = (int)(blockIdx.x >> 3) % nprob;
+    if (s >= g.T_s) return;
+    const int grp = blockIdx.y;
+    const RowsStateArgs& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    if (len <= 0) return;
+    const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
+    const char* __restrict__ A = pr.A + row0;
+    char* __restrict__ out = pr.out + row0;
+
+    {
+        const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+        for (int i = tid; i < D * 16; i += RS_NW * 64) {
+            float x[8];
+            int c, q;   // column of out, 16-byte piece (contracted indices 8q .. 8q+7)
+            if (pr.transpose_state) {
+                c = i >> 4;
+                q = i & 15;
+                const f32x4 a = *reinterpret_cast<const f32x4*>(st + c * D + 8 * q);
+                const f32x4 b = *reinterpret_cast<const f32x4*>(st + c * D + 8 * q + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+            } else {
+                q = i >> 7;
+                c = i & 127;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = st[(8 * q + e) * D + c];
+            }
+            const u32x4 pk = {pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7])};
+            *reinterpret_cast<u32x4*>(sW + tile_off(c, q)) = pk;
+        }
+    }
+    __syncthreads();
+
+    int nat[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) nat[ks] = tile_off(l32, 2 * ks + h);
+
+    // 32 rows of A as B-operand fragments (column = row of A, k = contracted index)
+    auto load_rows = [&](u32x4 (&dst)[8], int r) {
+        const bool ok = r < len;
+        const char* p = A + (size_t)r * ROWB + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            dst[ks] = ok ? *reinterpret_cast<const u32x4*>(p + 32 * ks) : z;
+        }
+    };
+
+    const int nit = (len + RS_NW * 32 - 1) / (RS_NW * 32);
+    u32x4 cur[8], nxt[8];
+    load_rows(cur, 32 * w + l32);
+    char* stg = sO + w * 4096;
+    for (int it = 0; it < nit; ++it) {
+        const int rbase = it * (RS_NW * 32) + 32 * w;
+        if (it + 1 < nit) load_rows(nxt, rbase + RS_NW * 32 + l32);
+
+        f32x16 Oacc[4];
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+        bf16x8 bufA[4], bufB[4];
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) bufA[tv] = lds_read16_at(sW + tv * (32 * ROWB), nat[0]);
+#pragma unroll
+        for (int ks = 0; ks < 8; ks += 2) {
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) bufB[tv] = lds_read16_at(sW + tv * (32 * ROWB), nat[ks + 1]);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], __builtin_bit_cast(bf16x8, cur[ks]), Oacc[tv]);
+            SCHED_FENCE();
+            if (ks + 2 < 8) {
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) bufA[tv] = lds_read16_at(sW + tv * (32 * ROWB), nat[ks + 2]);
+            }
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], __builtin_bit_cast(bf16x8, cur[ks + 1]), Oacc[tv]);
+            SCHED_FENCE();
+        }
+
+        // out^T tiles (lane = row) -> wave-private 4 KiB patch -> 16-byte row-contiguous stores,
+        // half of the 128 columns at a time (as in the fused pass)
+#pragma unroll
+        for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+            for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16& o = Oacc[2 * hv + tvv];
+                    u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                    *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                if (rbase + row < len)
+                    *reinterpret_cast<u32x4*>(out + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+            }
+        }
+        if (it + 1 < nit) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) cur[ks] = nxt[ks];
+        }
+    }
+}
+
 }  // namespace
 
 bool mfma_path_supported(const Geom& g, int dtype)
@@ -712,6 +851,23 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
     if (g.C == 256) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
+}
+
+hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, int n, hipStream_t st)
+{
+    constexpr int smem = D * ROWB + RS_NW * 4096;   // 64 KiB
+    RowsStateArgs a[3];
+    for (int i = 0; i < 3; ++i) {
+        const RowsStateProblem& p = probs[i < n ? i : 0];
+        a[i] = RowsStateArgs{static_cast<const char*>(p.A), p.state, static_cast<char*>(p.out), p.transpose_state};
+    }
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rows_state_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned gx = (unsigned)n * (((unsigned)g.T_s + 7u) & ~7u);
+    dim3 grid(gx, g.G), block(RS_NW * 64);
+    hipLaunchKernelGGL(rows_state_mfma_kernel, grid, block, smem, st, g, a[0], a[1], a[2], n);
+    return hipGetLastError();
 }
 
 }  // namespace lasp2

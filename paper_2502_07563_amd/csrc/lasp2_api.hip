@@ -186,6 +186,67 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     return from_hip(e);
 }
 
+int lasp2_state_total(const lasp2_desc_t* desc, const float* M, float* S, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({M, S});
+    if (rc != LASP2_OK) return rc;
+    return from_hip(launch_state_total(g, M, S, (hipStream_t)stream));
+}
+
+int lasp2_nomask_fwd(const lasp2_desc_t* desc, const void* Q, const float* S, void* O, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, S, O});
+    if (rc != LASP2_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (mfma_path_supported(g, desc->dtype)) {
+        const RowsStateProblem p = {Q, S, O, 0};
+        return from_hip(launch_rows_state_mfma(g, &p, 1, st));
+    }
+    return from_hip(launch_rows_state_generic(g, desc->dtype, Q, S, O, 0, st));
+}
+
+int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                     const void* dO, const float* S, void* dQ, void* dK, void* dV,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, K, V, dO, S, dQ, dK, dV, workspace});
+    if (rc != LASP2_OK) return rc;
+    size_t need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    if (workspace_bytes < need) return LASP2_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    float* dS = static_cast<float*>(workspace);
+    // dM_t = Q_t^T dO_t per slot, then the sum over the document's slots in place
+    hipError_t e = run_states(g, desc->dtype, Q, dO, dS, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    e = launch_state_total(g, dS, dS, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    if (mfma_path_supported(g, desc->dtype)) {
+        const RowsStateProblem p[3] = {{dO, S, dQ, 1}, {V, dS, dK, 1}, {K, dS, dV, 0}};
+        return from_hip(launch_rows_state_mfma(g, p, 3, st));
+    }
+    e = launch_rows_state_generic(g, desc->dtype, dO, S, dQ, 1, st);    // dQ = dO M^T
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    e = launch_rows_state_generic(g, desc->dtype, V, dS, dK, 1, st);    // dK = V dM^T
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    return from_hip(launch_rows_state_generic(g, desc->dtype, K, dS, dV, 0, st));   // dV = K dM
+}
+
 const char* lasp2_status_string(int status)
 {
     switch (status) {

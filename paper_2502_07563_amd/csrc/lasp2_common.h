@@ -67,6 +67,12 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const vo
 hipError_t launch_state_prefix(const Geom& g, const float* M, float* P, int reverse, int inclusive,
                                hipStream_t st);
 
+// S[s] = sum of M over the slots of s's document; S may alias M.
+hipError_t launch_state_total(const Geom& g, const float* M, float* S, hipStream_t st);
+// out = A * state[slot] (transpose_state: A * state[slot]^T), plain fp32-FMA kernel.
+hipError_t launch_rows_state_generic(const Geom& g, int dtype, const void* A, const float* state,
+                                     void* out, int transpose_state, hipStream_t st);
+
 // bf16 MFMA kernels (d = 128, C in {128,256}).
 bool mfma_path_supported(const Geom& g, int dtype);
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
@@ -79,5 +85,15 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
 hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
                                 const void* dO, const float* P, const float* dR, void* dQ, void* dK,
                                 void* dV, hipStream_t st);
+
+// Row-times-state products of the unmasked path, up to three in one launch:
+// out_i = A_i * state_i[slot] (or its transpose), i < n.
+struct RowsStateProblem {
+    const void* A;
+    const float* state;
+    void* out;
+    int transpose_state;
+};
+hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, int n, hipStream_t st);
 
 }  // namespace lasp2

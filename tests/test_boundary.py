@@ -32,7 +32,8 @@ def test_header_symbols_are_exported():
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(lasp2_[a-z0-9_]+)\s*\(", text))
     assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
-            "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string"} <= names
+            "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string", "lasp2_state_total",
+            "lasp2_nomask_fwd", "lasp2_nomask_bwd"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lasp2.h but not exported"
@@ -109,6 +110,15 @@ def test_null_and_alignment_errors_reach_no_device():
     need = ctypes.c_size_t(0)
     lib.lasp2_workspace_size(r, ctypes.byref(need))
     assert lib.lasp2_attn_bwd(r, *args, ctypes.c_size_t(need.value - 1), None) == -5
+    # the entry points without masking
+    assert lib.lasp2_state_total(r, FAKE, None, None) == -1
+    assert lib.lasp2_state_total(r, ODD, FAKE, None) == -6
+    assert lib.lasp2_nomask_fwd(r, FAKE, None, FAKE, None) == -1
+    assert lib.lasp2_nomask_fwd(r, FAKE, FAKE, ODD, None) == -6
+    for i in range(9):
+        a = list(args); a[i] = None
+        assert lib.lasp2_nomask_bwd(r, *a, ctypes.c_size_t(1 << 40), None) == -1
+    assert lib.lasp2_nomask_bwd(r, *args, ctypes.c_size_t(need.value - 1), None) == -5
 
 
 def test_empty_problem_is_ok_without_pointers():
@@ -119,3 +129,6 @@ def test_empty_problem_is_ok_without_pointers():
         assert lib.lasp2_state_prefix(r, None, None, 0, None) == 0
         assert lib.lasp2_attn_fwd(r, None, None, None, None, None, None) == 0
         assert lib.lasp2_attn_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0
+        assert lib.lasp2_state_total(r, None, None, None) == 0
+        assert lib.lasp2_nomask_fwd(r, None, None, None, None) == 0
+        assert lib.lasp2_nomask_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0

@@ -111,3 +111,38 @@ def test_cfg5_packed_documents(oracle):
     rng = np.random.default_rng(5)
     _check_group(oracle, cfg, cu, out, 0, full=True, n_rows=32, rng=rng)
     _check_group(oracle, cfg, cu, out, 31, full=False, n_rows=32, rng=rng)
+
+
+def test_cfg3_without_masking(oracle):
+    """The unmasked entry points at the size bench.py times (N=262144, 64 slots per head): sampled
+    rows of O, dQ, dK, dV of two heads against the definition, and the totals of those heads."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    cfg = synth.CONFIGS["cfg3"]
+    B, H, N, d, C, L, dtype, seed = (cfg[k] for k in ("B", "H", "N", "d", "C", "L", "dtype", "seed"))
+    p = bd.Problem(B, H, N, d, C, L, dtype)
+    dev = {}
+    for n in ("Q", "K", "V", "dO"):
+        host = synth.gen_tensor(seed, n, B * H, N, d, dtype, workers=16)
+        dev[n] = torch.from_numpy(host).reshape(B, H, N, d).to("cuda").to(p.torch_dtype)
+        del host
+    O, S = bd.nomask_forward(p, dev["Q"], dev["K"], dev["V"])
+    dQ, dK, dV, dS = bd.nomask_backward(p, dev["Q"], dev["K"], dev["V"], dev["dO"], S)
+    torch.cuda.synchronize()
+    out = dict(O=O, dQ=dQ, dK=dK, dV=dV)
+    rng = np.random.default_rng(33)
+    bounds, first = slot_partition(N, L, None)
+    for g in (3, 12):
+        x = _host_group(cfg, g)
+        rows = np.unique(np.concatenate([rng.integers(0, N, 24), [0, N - 1, L - 1, L]])).astype(np.int64)
+        errs = {}
+        for which, k in enumerate(("O", "dQ", "dK", "dV")):
+            ref = oracle.nomask_def_rows(x["Q"], x["K"], x["V"], x["dO"], rows, which)
+            errs[k] = rel_l2(_gpu_group(out[k], g)[rows], ref)
+            assert errs[k] <= TOL[dtype], (g, errs)
+        S_ref = oracle.state_total(oracle.chunk_states(x["K"][None], x["V"][None], bounds), first)
+        dS_ref = oracle.state_total(oracle.chunk_states(x["Q"][None], x["dO"][None], bounds), first)
+        errs["S"] = rel_l2(_gpu_group(S, g), S_ref[0])
+        errs["dS"] = rel_l2(_gpu_group(dS, g), dS_ref[0])
+        assert max(errs["S"], errs["dS"]) <= TOL_STATE, (g, errs)
+        print(f"group {g}:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)

@@ -150,3 +150,18 @@ def test_invariant_under_joint_permutation_of_keys_and_values(oracle):
     full = oracle.nomask_fwd_def(Q, K, V)
     assert _rel(oracle.nomask_fwd_def(Q, K[:, perm], V[:, perm]), full) < 1e-13
     assert _rel(oracle.fwd_def(Q, K[:, perm], V[:, perm]), oracle.fwd_def(Q, K, V)) > 1e-3
+
+
+def test_row_sampler_matches_full_definition(oracle):
+    cu = [0, 7, 8, 40, 61]
+    Q, K, V, dO = _rand(1, 61, 8, 21)
+    full = (oracle.nomask_fwd_def(Q, K, V, cu),) + oracle.nomask_bwd_def(Q, K, V, dO, cu)
+    rows = np.array([60, 0, 7, 8, 39, 40, 6])
+    for which in range(4):
+        got = oracle.nomask_def_rows(Q[0], K[0], V[0], dO[0], rows, which, cu)
+        assert _rel(got, full[which][0][rows]) < 1e-13
+    g = json.load(open(os.path.join(GOLD, "nomask_hand_example.json")))
+    A = {k: np.array(g[k], dtype=np.float64) for k in g if not k.startswith("_")}
+    for which, key in enumerate(("O", "dQ", "dK", "dV")):
+        got = oracle.nomask_def_rows(A["Q"], A["K"], A["V"], A["dO"], np.array([2, 0, 1]), which)
+        assert np.array_equal(got, A[key][[2, 0, 1]])
