@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--slot-len", type=int, default=None,
+                    help="tokens per state slot L (a multiple of C) instead of the workload's own; "
+                         "L = N is the serial-carry schedule with one slot per head")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -78,6 +81,8 @@ def main():
 
     cfg = synth.CONFIGS[args.workload]
     B, H, N, d, C, L = (cfg[k] for k in ("B", "H", "N", "d", "C", "L"))
+    if args.slot_len is not None:
+        L = args.slot_len
     dtype = cfg["dtype"]
     cu = synth.config_offsets(cfg)
     dev = torch.device("cuda:0")

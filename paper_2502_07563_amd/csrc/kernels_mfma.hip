@@ -399,11 +399,13 @@ __device__ __forceinline__ void inter_product(f32x16 (&Oacc)[4], const char* sM,
     }
 }
 
-// The grid carries nprob problems that walk the same slots: workgroup x handles slot
+// The grid is one-dimensional and carries nprob problems that walk the same slots.  The
+// (group, slot) pairs are numbered unit = group * T_s + slot, and workgroup x handles unit
 // 8*(x/(8 nprob)) + x%8 of problem (x/8)%nprob.  With workgroups dealt to the eight XCDs
-// round-robin, the nprob workgroups of a slot land on the same XCD and run at about the same
-// time, so a block of a tensor that several problems stream (the three backward problems all
-// walk forward over Q, K, V, dO) comes from HBM once and from that XCD's L2 afterwards.
+// round-robin, consecutive units go to different XCDs whatever T_s is (one slot per head
+// included), while the nprob workgroups of a unit land on the same XCD and run at about the
+// same time, so a block of a tensor that several problems stream (the three backward problems
+// all walk forward over Q, K, V, dO) comes from HBM once and from that XCD's L2 afterwards.
 //
 // Walk: chunks in ascending order in both modes.
 //   causal: the accumulators hold S_c = prefix state before chunk c; snapshot and inter-chunk
@@ -428,10 +430,10 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int s = (int)(blockIdx.x / (8u * nprob)) * 8 + (int)(blockIdx.x & 7u);
+    const unsigned unit = (blockIdx.x / (8u * nprob)) * 8u + (blockIdx.x & 7u);
     const int prob = (int)(blockIdx.x >> 3) % nprob;
-    if (s >= g.T_s) return;
-    const int grp = blockIdx.y;
+    if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
+    const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
     const AttnProblem& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
     const char* __restrict__ A = pr.A;
     const char* __restrict__ Bk = pr.Bk;
@@ -658,8 +660,9 @@ hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    const unsigned gx = (unsigned)nprob * (((unsigned)g.T_s + 7u) & ~7u);
-    dim3 grid(gx, g.G), block(C * 2);
+    const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
+    const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
+    dim3 grid(gx), block(C * 2);
     hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, p2, nprob);
     return hipGetLastError();
 }
@@ -699,10 +702,10 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
     // same workgroup-to-slot mapping as the fused pass: the nprob products of a slot share an XCD
-    const int s = (int)(blockIdx.x / (8u * nprob)) * 8 + (int)(blockIdx.x & 7u);
+    const unsigned unit = (blockIdx.x / (8u * nprob)) * 8u + (blockIdx.x & 7u);
     const int prob = (int)(blockIdx.x >> 3) % nprob;
-    if (s >= g.T_s) return;
-    const int grp = blockIdx.y;
+    if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
+    const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
     const RowsStateArgs& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
     int tok0, len;
     slot_range(g, s, tok0, len);
@@ -864,8 +867,9 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rows_state_mfma_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    const unsigned gx = (unsigned)n * (((unsigned)g.T_s + 7u) & ~7u);
-    dim3 grid(gx, g.G), block(RS_NW * 64);
+    const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
+    const unsigned gx = (unsigned)n * ((units + 7u) & ~7u);
+    dim3 grid(gx), block(RS_NW * 64);
     hipLaunchKernelGGL(rows_state_mfma_kernel, grid, block, smem, st, g, a[0], a[1], a[2], n);
     return hipGetLastError();
 }

@@ -48,6 +48,8 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     }
     if (T_s > INT32_MAX) return LASP2_ERR_SHAPE;
     if (G > 0 && T_s > (INT64_MAX / 8) / (G * desc->d * desc->d)) return LASP2_ERR_SHAPE;
+    // one-dimensional grids carry up to three workgroups per (group, slot) pair
+    if (G * T_s > (int64_t)(INT32_MAX / 4)) return LASP2_ERR_SHAPE;
 
     g->G = (int32_t)G;
     g->N = desc->N;
