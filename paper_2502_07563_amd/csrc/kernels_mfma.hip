@@ -224,6 +224,13 @@ __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* 
 // per stage, memory operations retire in order, and at least the DPS loads of the next
 // stage were issued after those of the stage about to be read, so vmcnt(DPS) is always
 // sufficient (extra loads or stores issued in between only make the wait stricter).
+//
+// The rows of A for the next chunk are fetched the same way (asm loads into registers,
+// completed by a counted wait at the chunk's end), so that inside the walk the compiler
+// places no vector-memory wait of its own: it cannot see the stage loads, and any wait it
+// inserted for a load it does know would drain them all.  For the same reason the kernel
+// must not spill (a reload from scratch is such a load); tests/test_isa_guards.py checks
+// both properties on the compiled code.
 // =====================================================================================
 constexpr int NSTAGE = 3;
 
@@ -232,36 +239,44 @@ __device__ __forceinline__ uint32_t lds_addr_of(const char* p)
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-__device__ __forceinline__ void dma16(const char* gptr, uint32_t lds_base)
+// One wave instruction of direct global->LDS load: lane l fetches the 16 bytes at sbase + voff
+// (sbase and lds_base uniform, held in scalar registers; voff per lane) into LDS at
+// lds_base + 16 l.
+__device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_base)
 {
-    // lds_base is the same in every lane of the wave; readfirstlane moves it to a scalar register
-    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
+// Byte offset, inside a block of rows that starts at a multiple of 16, of the 16 bytes that lane
+// `lane` of wave instruction `k` (rows 4k .. 4k+3) must fetch so that they land swizzled.
+__device__ __forceinline__ uint32_t dma_lane_off(int k, int lane)
 {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    const int r = 4 * k + (lane >> 4);
+    return (uint32_t)(r * ROWB + (((lane & 15) ^ swz(r)) << 4));
 }
 
 // Issue the loads of one 64-token block (rows tok .. tok+63 of the slot) of X and Y into the
-// stage tiles tx, ty.  Rows past the slot's end are fetched from its last row (always in
-// bounds) and zeroed afterwards by zero_tail_rows().
+// stage tiles tx, ty; dvo[u] = dma_lane_off(w * IPW + u, lane), computed once per kernel.
+// Rows past the slot's end are fetched from its last row (always in bounds) and zeroed
+// afterwards by zero_tail_rows().
 template <int NW>
 __device__ __forceinline__ void dma_block(const char* X, const char* Y, size_t row0_bytes, int tok,
-                                          int len, char* tx, char* ty, int w, int lane)
+                                          int len, char* tx, char* ty, int w, int lane,
+                                          const uint32_t (&dvo)[16 / NW])
 {
     constexpr int IPW = 16 / NW;   // wave instructions per tensor per stage
+    const size_t blk = row0_bytes + (size_t)tok * ROWB;
+    const bool full = tok + KB <= len;
 #pragma unroll
     for (int u = 0; u < IPW; ++u) {
-        const int rowbase = 4 * (w * IPW + u);
-        const int r = rowbase + (lane >> 4);
-        const int lc = (lane & 15) ^ swz(r);
-        const int gr = min(tok + r, len - 1);
-        const size_t off = row0_bytes + (size_t)gr * ROWB + lc * 16;
-        dma16(X + off, lds_addr_of(tx + rowbase * ROWB));
-        dma16(Y + off, lds_addr_of(ty + rowbase * ROWB));
+        const int k = w * IPW + u;
+        uint32_t voff = dvo[u];
+        if (!full) {
+            const int r = 4 * k + (lane >> 4);
+            voff = (uint32_t)(min(r, len - 1 - tok) * ROWB + (int)(voff & (ROWB - 1)));
+        }
+        dma16(X + blk, voff, lds_addr_of(tx + 4 * k * ROWB));
+        dma16(Y + blk, voff, lds_addr_of(ty + 4 * k * ROWB));
     }
 }
 
@@ -278,6 +293,31 @@ __device__ __forceinline__ void zero_tail_rows(int tok, int len, char* tx, char*
             *reinterpret_cast<u32x4*>(ty + r * ROWB + (lane & 15) * 16) = z;
         }
     }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Global loads whose completion the kernel tracks itself.  The compiler knows nothing of them, so
+// it neither counts them nor waits for them: the destination registers hold the data only
+// after the matching wait_vmcnt_token().  That wait returns a zero the compiler cannot see
+// through; every expression that reads the loaded registers must also depend on this value,
+// which keeps all such reads behind the wait.
+template <int OFF>
+__device__ __forceinline__ void gload16_async(u32x4& dst, const char* p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(dst) : "v"(p), "n"(OFF) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ uint32_t wait_vmcnt_token()
+{
+    uint32_t zero;
+    asm volatile("s_waitcnt vmcnt(%1)\n\tv_mov_b32 %0, 0" : "=v"(zero) : "n"(N) : "memory");
+    return zero;
 }
 
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -428,7 +468,9 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
     char* sO = sM + D * ROWB;                     // output staging, 4 KiB per wave
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index is the same in all 64 lanes: keep it, and all that derives from it, scalar
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, l32 = lane & 31;
     const unsigned unit = (blockIdx.x / (8u * nprob)) * 8u + (blockIdx.x & 7u);
     const int prob = (int)(blockIdx.x >> 3) % nprob;
@@ -454,9 +496,12 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
     const int nch = (len + C - 1) / C;
     const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
+    uint32_t dvo[16 / NW];   // per-lane source offsets of this wave's stage loads
+#pragma unroll
+    for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
     auto issue = [&](int i) {
         dma_block<NW>(Bk, Cv, row0, i * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
-                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane);
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane, dvo);
     };
     issue(0);
     if (NB > 1) issue(1);
@@ -487,19 +532,30 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     LaneOffs<TPW> lo;
     make_lane_offs<TPW>(lo, lane, t0);
 
-    bf16x8 qf[8];   // this wave's 32 rows of A as B-operand fragments (column = row of A, k = d)
-    auto load_q = [&](int c) {
-        const int r = c * C + 32 * rb + l32;
-        const bool ok = r < len;
+    // This wave's 32 rows of A as B-operand fragments (column = row of A, k = d).  The rows of
+    // the next chunk are requested into tq once the current chunk has made its last use of qf;
+    // rows past the slot's end fetch its last row (they only feed output rows that are not stored).
+    u32x4 qv[8];
+    auto issue_q = [&](int c) {
+        const int r = min(c * C + 32 * rb + l32, len - 1);
         const char* p = A + row0 + (size_t)r * ROWB + 16 * h;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            u32x4 z = {0u, 0u, 0u, 0u};
-            u32x4 x = ok ? *reinterpret_cast<const u32x4*>(p + 32 * ks) : z;
-            qf[ks] = __builtin_bit_cast(bf16x8, x);
-        }
+        gload16_async<0>(qv[0], p);
+        gload16_async<32>(qv[1], p);
+        gload16_async<64>(qv[2], p);
+        gload16_async<96>(qv[3], p);
+        gload16_async<128>(qv[4], p);
+        gload16_async<160>(qv[5], p);
+        gload16_async<192>(qv[6], p);
+        gload16_async<224>(qv[7], p);
     };
-    load_q(0);
+    auto take_q = [&](uint32_t zero) {
+        const u32x4 z = {zero, zero, zero, zero};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qv[ks] = qv[ks] | z;
+    };
+    issue_q(0);
+    take_q(wait_vmcnt_token<0>());
+    const bf16x8 (&qf)[8] = reinterpret_cast<const bf16x8 (&)[8]>(qv);
 
     int bi = 0;          // index of the block being consumed
     int prev_nblk = BPC;
@@ -524,7 +580,13 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
             char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
             // this wave's loads of block bi have landed (those of bi+1 may still fly)
-            if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            // In the first two blocks after a chunk boundary the previous chunk's eight stores
+            // were also issued after these loads, and need not have completed.
+            if (c > 0 && jb < 2) {
+                if (bi + 1 < NB) wait_vmcnt<DPS + 8>(); else wait_vmcnt<8>();
+            } else {
+                if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            }
             if (bi * KB + KB > len) zero_tail_rows<NW>(bi * KB, len, tK, tV, w, lane);
             __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
             if (bi + 2 < NB) issue(bi + 2);
@@ -590,7 +652,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
             // causal: the rows of the next chunk replace qf while the state update and the
             // store run (anti-causal still needs qf for the inter product at the chunk's end)
-            if (!anti && jb + 1 == nblk && !last_chunk) load_q(c + 1);
+            if (!anti && jb + 1 == nblk && !last_chunk) issue_q(c + 1);
             if (anti || !last_chunk) {
                 // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
                 rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
@@ -618,7 +680,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
             __syncthreads();
             inter_product<NOP>(Oacc, sM, qf, lo.nat);
-            if (!last_chunk) load_q(c + 1);
+            if (!last_chunk) issue_q(c + 1);
         }
 
         // Store this wave's 32 output rows.  The accumulators hold out^T (lane = row, four
@@ -647,6 +709,9 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
                 }
             }
         }
+        // Only the eight stores above were issued after the rows of A for the next chunk (they
+        // all execute: a chunk that is not the last is full).
+        if (!last_chunk) take_q(wait_vmcnt_token<8>());
     }
 }
 

@@ -1,0 +1,97 @@
+"""Guards on the compiled attention kernel that no parity test can give: properties of the
+generated gfx950 code the kernel's hand-managed memory waits rely on.  Compiles the kernel file
+to assembly with the flags of the real build (no GPU needed) and checks, for every instantiation
+of attn_mfma_kernel:
+  * it uses no scratch memory (a spilled register would be reloaded with a vector-memory load the
+    explicit wait counts do not account for, and a spill of a register that an in-flight load is
+    about to write would save stale data);
+  * between the asm-issued loads of the next chunk's rows and the counted wait that completes them,
+    nothing reads or overwrites their destination registers except the inter-chunk product of the
+    anti-causal walk (which runs before that walk issues its own loads);
+  * the only vmcnt waits after the prologue are the kernel's own (they sit inside asm blocks)."""
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2502_07563_amd", "csrc")
+
+
+@pytest.fixture(scope="module")
+def isa(tmp_path_factory):
+    from paper_2502_07563_amd import build as b
+    out = tmp_path_factory.mktemp("isa") / "kernels_mfma.s"
+    flags = [f for f in b.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), *flags, "-S", "--cuda-device-only",
+           "-o", str(out), os.path.join(SRC, "kernels_mfma.hip")]
+    subprocess.run(cmd, check=True, capture_output=True)
+    return open(out).read().split("\n")
+
+
+def _kernels(lines):
+    for i, l in enumerate(lines):
+        m = re.match(r"^(_ZN.*attn_mfma_kernelILi(\d+).*):", l)
+        if m:
+            end = next(j for j in range(i, len(lines)) if "s_endpgm" in lines[j])
+            yield m.group(2), lines[i:end], m.group(1)
+
+
+def _regs(text):
+    out = set()
+    for m in re.finditer(r"v\[(\d+):(\d+)\]|\bv(\d+)\b", text):
+        out |= {int(m.group(3))} if m.group(3) else set(range(int(m.group(1)), int(m.group(2)) + 1))
+    return out
+
+
+def test_attention_kernels_do_not_spill(isa):
+    text = "\n".join(isa)
+    found = 0
+    for cname, body, sym in _kernels(isa):
+        found += 1
+        assert not any("scratch_" in l for l in body), f"attn_mfma_kernel<{cname}> touches scratch memory"
+        m = re.search(r"\.amdhsa_kernel " + re.escape(sym) + r".*?\.amdhsa_private_segment_fixed_size (\d+)",
+                      text, flags=re.S)
+        assert m and int(m.group(1)) == 0, f"attn_mfma_kernel<{cname}> has a private segment"
+    assert found == 2
+
+
+def test_in_flight_row_registers_are_left_alone(isa):
+    for cname, body, _ in _kernels(isa):
+        in_asm, asm_loads, asm_waits = False, [], []
+        for i, l in enumerate(body):
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif in_asm and "global_load_dwordx4" in l:
+                asm_loads.append((i, _regs(l.split(",")[0])))
+            elif in_asm and "s_waitcnt vmcnt" in l:
+                asm_waits.append(i)
+        assert len(asm_loads) == 24, (cname, len(asm_loads))     # prologue, causal site, anti-causal site
+        token = [i for i in asm_waits if "vmcnt(8)" in body[i] and i > asm_loads[-1][0]]
+        assert len(token) == 1, (cname, token)
+        dest = set().union(*(r for _, r in asm_loads[8:]))
+        assert len(dest) == 32
+        causal_last, anti_first, anti_last = asm_loads[15][0], asm_loads[16][0], asm_loads[23][0]
+        for i in range(causal_last + 1, token[0]):
+            l = body[i].strip()
+            if not l or l.startswith(";") or not (_regs(l) & dest):
+                continue
+            if anti_first <= i <= anti_last and "global_load_dwordx4" in l:
+                continue                         # the anti-causal walk's own loads
+            assert i < anti_first and l.startswith("v_mfma"), (cname, i, l)
+
+
+def test_no_compiler_placed_vmcnt_wait_in_the_walk(isa):
+    for cname, body, _ in _kernels(isa):
+        first_barrier = next(i for i, l in enumerate(body) if "s_barrier" in l)
+        in_asm = False
+        for i, l in enumerate(body):
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif "vmcnt" in l and i > first_barrier:
+                assert in_asm, (cname, i, l.strip())
