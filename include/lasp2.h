@@ -49,7 +49,8 @@
  *   - B, H or N equal to 0 is a valid empty problem: the call returns LASP2_OK
  *     and launches nothing (pointers are then not examined).
  *   - Supported: d in {16, 32, 64, 128}; 1 <= C <= 512.  The MFMA kernels
- *     cover bf16, d = 128, C in {128, 256}; any other supported
+ *     cover bf16 with d = 128 for every C (they tile a slot in chunks of
+ *     their own, which the result does not depend on); any other supported
  *     combination runs the plain fp32-FMA kernels.  There is no CPU fallback.
  */
 #ifndef LASP2_H

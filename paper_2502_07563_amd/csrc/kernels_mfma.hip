@@ -1,5 +1,5 @@
-// bf16 MFMA kernels of liblasp2 for gfx950 (d = 128): chunk states and the fused
-// intra + inter attention pass.  One workgroup walks the chunks of one state slot and
+// bf16 MFMA kernels of liblasp2 for gfx950 (d = 128, any chunk length C): chunk states and the
+// fused intra + inter attention pass.  One workgroup walks the chunks of one state slot and
 // carries the running d x d state in fp32 MFMA accumulators.
 //
 // Operand conventions (v_mfma_f32_32x32x16_bf16, wave of 64 lanes, h = lane/32):
@@ -39,11 +39,6 @@ __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >>
 __device__ __forceinline__ int tile_off(int row, int chunk)
 {
     return row * ROWB + (((chunk ^ swz(row)) & 15) << 4);
-}
-
-__device__ __forceinline__ bf16x8 lds_read16(const char* tile, int row, int chunk)
-{
-    return *reinterpret_cast<const bf16x8*>(tile + tile_off(row, chunk));
 }
 
 // Transposed fetch of 8 k-values for an MFMA operand whose k axis is the tile's row axis.
@@ -732,6 +727,9 @@ hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem
     return hipGetLastError();
 }
 
+// Internal chunk of the fused pass: 256 rows (eight waves) unless no slot is longer than 128.
+bool wide_chunks(const Geom& g) { return g.L > 128; }
+
 AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const float* state, void* out,
                          int transpose_state, int anti)
 {
@@ -883,7 +881,9 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
 
 bool mfma_path_supported(const Geom& g, int dtype)
 {
-    return dtype == LASP2_BF16 && g.d == D && (g.C == 256 || g.C == 128);
+    // The kernels tile a slot in their own chunks (the result does not depend on the chunk
+    // length), so every C of the caller is served.
+    return dtype == LASP2_BF16 && g.d == D;
 }
 
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M, hipStream_t st)
@@ -902,7 +902,7 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
                                 const float* P, void* O, hipStream_t st)
 {
     const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
-    if (g.C == 256) return launch_attn_C<256>(g, p, p, p, 1, st);
+    if (wide_chunks(g)) return launch_attn_C<256>(g, p, p, p, 1, st);
     return launch_attn_C<128>(g, p, p, p, 1, st);
 }
 
@@ -917,7 +917,7 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pq = make_problem(dO, V, K, P, dQ, 1, 0);
     const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
-    if (g.C == 256) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
+    if (wide_chunks(g)) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }
 

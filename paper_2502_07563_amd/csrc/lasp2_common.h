@@ -73,7 +73,7 @@ hipError_t launch_state_total(const Geom& g, const float* M, float* S, hipStream
 hipError_t launch_rows_state_generic(const Geom& g, int dtype, const void* A, const float* state,
                                      void* out, int transpose_state, hipStream_t st);
 
-// bf16 MFMA kernels (d = 128, C in {128,256}).
+// bf16 MFMA kernels (d = 128; they tile slots in their own chunks, so any C).
 bool mfma_path_supported(const Geom& g, int dtype);
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
                               hipStream_t st);

@@ -75,7 +75,8 @@ def test_fp32_shapes(oracle, N, d, C, L):
 
 
 @pytest.mark.parametrize("N,C,L", [(2048, 256, 0), (2304, 256, 1024), (1900, 256, 512), (200, 256, 0),
-                                   (1536, 128, 512), (1000, 64, 256)])
+                                   (1536, 128, 512), (1000, 64, 256), (777, 50, 150), (640, 512, 0),
+                                   (67, 1, 3), (1024, 32, 128)])
 def test_bf16_d128(oracle, N, C, L):
     """The MFMA path's shapes (bf16, d=128): several chunks per slot, ragged tails."""
     _run_all(oracle, 1, 3, N, 128, C, L, "bf16", seed=20 + N)
