@@ -285,3 +285,127 @@ def nomask_backward_by_algorithm(Q, K, V, dO, bounds, first=None):
     dK = rows_times_state(V, dS, bounds, transpose=True)
     dV = rows_times_state(K, dS, bounds)
     return dQ, dK, dV, dS
+
+
+# ---------------------------------------------------------------------------
+# Scalar decay: lam is one factor in (0, 1] per group (shape [G]); lam = 1 is the plain case.
+# ---------------------------------------------------------------------------
+
+def _lam(lam, G):
+    lam = np.ascontiguousarray(np.broadcast_to(np.asarray(lam, dtype=np.float64), (G,)))
+    assert np.all(lam > 0) and np.all(lam <= 1), "decay factors must lie in (0, 1]"
+    return lam, lam.ctypes.data_as(_c_dp)
+
+
+def fwd_def_decay(Q, K, V, lam, cu=None):
+    """O_i = sum_{j<=i} lam^(i-j) (q_i . k_j) v_j, brute force."""
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    O = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N)); lam, lp = _lam(lam, G)
+    _lib().lasp2_oracle_fwd_def_decay(q, k, v, O.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                      ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1), lp)
+    return O
+
+
+def bwd_def_decay(Q, K, V, dO, lam, cu=None):
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO)
+    dQ = np.empty((G, N, d)); dK = np.empty((G, N, d)); dV = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N)); lam, lp = _lam(lam, G)
+    _lib().lasp2_oracle_bwd_def_decay(q, k, v, g, dQ.ctypes.data_as(_c_dp), dK.ctypes.data_as(_c_dp),
+                                      dV.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                      ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1), lp)
+    return dQ, dK, dV
+
+
+def fwd_rec_decay(Q, K, V, lam, cu=None):
+    """M_s = lam M_{s-1} + k_s^T v_s, o_s = q_s M_s."""
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    O = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N)); lam, lp = _lam(lam, G)
+    _lib().lasp2_oracle_fwd_rec_decay(q, k, v, O.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                      ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1), lp)
+    return O
+
+
+def bwd_rec_decay(Q, K, V, dO, lam, cu=None):
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO)
+    dQ = np.empty((G, N, d)); dK = np.empty((G, N, d)); dV = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N)); lam, lp = _lam(lam, G)
+    _lib().lasp2_oracle_bwd_rec_decay(q, k, v, g, dQ.ctypes.data_as(_c_dp), dK.ctypes.data_as(_c_dp),
+                                      dV.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                      ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1), lp)
+    return dQ, dK, dV
+
+
+def chunk_states_decay(X, Y, bounds, lam, anchor_start=False):
+    """Decayed chunk states, anchored at each chunk's last token (or its first)."""
+    G, N, d = _gnd(X)
+    X, x = _d(X); Y, y = _d(Y)
+    b, bp = _l(_bounds(bounds, N)); lam, lp = _lam(lam, G)
+    T = len(b) - 1
+    M = np.empty((G, T, d, d))
+    _lib().lasp2_oracle_chunk_states_decay(x, y, M.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                           ctypes.c_long(d), bp, ctypes.c_long(T), lp,
+                                           ctypes.c_int(1 if anchor_start else 0))
+    return M
+
+
+def state_prefix_decay(M, bounds, lam, first=None, reverse=False):
+    """Decayed exclusive combine of [G, T, d, d] states over the chunk partition `bounds`."""
+    G, T, d, d2 = M.shape
+    assert d == d2
+    M, m = _d(M)
+    b, bp = _l(np.asarray(bounds, dtype=np.int64)); lam, lp = _lam(lam, G)
+    assert len(b) == T + 1
+    P = np.empty_like(M)
+    if first is None:
+        fp = None
+    else:
+        first = np.ascontiguousarray(first, dtype=np.int32)
+        assert first.shape == (T,)
+        fp = first.ctypes.data_as(_c_ip)
+    _lib().lasp2_oracle_state_prefix_decay(m, P.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(T),
+                                           ctypes.c_long(d), fp, ctypes.c_int(1 if reverse else 0), bp, lp)
+    return P
+
+
+def attn_fwd_chunked_decay(Q, K, V, P, bounds, lam):
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); P, p = _d(P)
+    b, bp = _l(_bounds(bounds, N)); lam, lp = _lam(lam, G)
+    O = np.zeros((G, N, d))
+    _lib().lasp2_oracle_attn_fwd_chunked_decay(q, k, v, p, O.ctypes.data_as(_c_dp), ctypes.c_long(G),
+                                               ctypes.c_long(N), ctypes.c_long(d), bp,
+                                               ctypes.c_long(len(b) - 1), lp)
+    return O
+
+
+def attn_bwd_chunked_decay(Q, K, V, dO, P, dP, bounds, lam):
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO); P, p = _d(P); dP, dp = _d(dP)
+    b, bp = _l(_bounds(bounds, N)); lam, lp = _lam(lam, G)
+    dQ = np.zeros((G, N, d)); dK = np.zeros((G, N, d)); dV = np.zeros((G, N, d))
+    _lib().lasp2_oracle_attn_bwd_chunked_decay(q, k, v, g, p, dp, dQ.ctypes.data_as(_c_dp),
+                                               dK.ctypes.data_as(_c_dp), dV.ctypes.data_as(_c_dp),
+                                               ctypes.c_long(G), ctypes.c_long(N), ctypes.c_long(d), bp,
+                                               ctypes.c_long(len(b) - 1), lp)
+    return dQ, dK, dV
+
+
+def forward_by_algorithm_decay(Q, K, V, bounds, lam, first=None):
+    """Decayed forward steps: states (end-anchored) -> decayed prefix -> intra + inter."""
+    M = chunk_states_decay(K, V, bounds, lam)
+    P = state_prefix_decay(M, bounds, lam, first, reverse=False)
+    return attn_fwd_chunked_decay(Q, K, V, P, bounds, lam), M, P
+
+
+def backward_by_algorithm_decay(Q, K, V, dO, bounds, lam, first=None):
+    """Decayed backward steps: dM (start-anchored) -> decayed suffix -> intra + inter."""
+    P = state_prefix_decay(chunk_states_decay(K, V, bounds, lam), bounds, lam, first, reverse=False)
+    dM = chunk_states_decay(Q, dO, bounds, lam, anchor_start=True)
+    dP = state_prefix_decay(dM, bounds, lam, first, reverse=True)
+    return attn_bwd_chunked_decay(Q, K, V, dO, P, dP, bounds, lam) + (dM, dP)

@@ -28,6 +28,11 @@
  *               the steps of Algorithm "LASP-2 w/ Masking" and its backward,
  *               in the paper's order, over an arbitrary partition of the
  *               tokens into chunks.
+ *   *_decay      : the same three families for scalar decay (one factor lam in (0,1] per
+ *               group, mask entries lam^(i-j) instead of 1), the form the Retention and
+ *               Lightning Attention layers of the paper's Table 2 use; the paper prints no
+ *               formulas for them, so the definition below is the reference and the
+ *               recurrence and chunked steps are derived from it.
  *   nomask_*_def / state_total / rows_times_state :
  *               linear attention without the mask (every token of a document
  *               attends to every token of it): the double-sum definition and
@@ -41,6 +46,7 @@
  *     attention).
  */
 #include <stdlib.h>
+#include <math.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -577,4 +583,299 @@ void lasp2_oracle_nomask_def_rows(const double* Q, const double* K, const double
         }
     }
     free(doc);
+}
+
+/* ================================================================== */
+/* Scalar decay.  lam[g] in (0,1] per group; lam == 1 is the plain case. */
+/* Definition: O[i,:] = sum_{j<=i, same doc} lam^(i-j) (q_i.k_j) v_j     */
+/* ================================================================== */
+void lasp2_oracle_fwd_def_decay(const double* Q, const double* K, const double* V,
+                                double* O, long G, long N, long d,
+                                const long* cu, long n_docs, const double* lam)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            double* o = O + (g * N + i) * d;
+            for (long b = 0; b < d; ++b) o[b] = 0.0;
+            for (long j = cu[doc[i]]; j <= i; ++j) {
+                double s = pow(lam[g], (double)(i - j)) * dot(Q + (g * N + i) * d, K + (g * N + j) * d, d);
+                const double* v = V + (g * N + j) * d;
+                for (long b = 0; b < d; ++b) o[b] += s * v[b];
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Gradient of <dO, O> under the decayed definition, as double sums:
+ *   dQ[i,:] = sum_{j<=i} lam^(i-j) (dO_i.v_j) k_j
+ *   dK[j,:] = sum_{i>=j} lam^(i-j) (dO_i.v_j) q_i
+ *   dV[j,:] = sum_{i>=j} lam^(i-j) (q_i.k_j) dO_i
+ */
+void lasp2_oracle_bwd_def_decay(const double* Q, const double* K, const double* V,
+                                const double* dO, double* dQ, double* dK, double* dV,
+                                long G, long N, long d, const long* cu, long n_docs,
+                                const double* lam)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            long lo = cu[doc[i]], hi = cu[doc[i] + 1];
+            double* dq = dQ + (g * N + i) * d;
+            double* dk = dK + (g * N + i) * d;
+            double* dv = dV + (g * N + i) * d;
+            for (long a = 0; a < d; ++a) { dq[a] = 0.0; dk[a] = 0.0; dv[a] = 0.0; }
+            for (long j = lo; j <= i; ++j) {         /* i as a query */
+                double w = pow(lam[g], (double)(i - j));
+                double gij = w * dot(dO + (g * N + i) * d, V + (g * N + j) * d, d);
+                const double* kj = K + (g * N + j) * d;
+                for (long a = 0; a < d; ++a) dq[a] += gij * kj[a];
+            }
+            for (long r = i; r < hi; ++r) {          /* i as a key/value of the later query r */
+                double w = pow(lam[g], (double)(r - i));
+                double gri = w * dot(dO + (g * N + r) * d, V + (g * N + i) * d, d);
+                double sri = w * dot(Q + (g * N + r) * d, K + (g * N + i) * d, d);
+                const double* qr = Q + (g * N + r) * d;
+                const double* dor = dO + (g * N + r) * d;
+                for (long a = 0; a < d; ++a) { dk[a] += gri * qr[a]; dv[a] += sri * dor[a]; }
+            }
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Recurrent form with decay: M_s = lam M_{s-1} + k_s^T v_s, o_s = q_s M_s (state cleared at
+ * each document start); backward: dq_s = dO_s M_s^T, adjoint D_s = lam D_{s+1} + q_s^T dO_s
+ * (cleared at each document end), dk_s = v_s D_s^T, dv_s = k_s D_s.
+ */
+void lasp2_oracle_fwd_rec_decay(const double* Q, const double* K, const double* V, double* O,
+                                long G, long N, long d, const long* cu, long n_docs,
+                                const double* lam)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* M = (double*)malloc(sizeof(double) * (size_t)(d * d));
+        for (long k = 0; k < n_docs; ++k) {
+            memset(M, 0, sizeof(double) * (size_t)(d * d));
+            for (long s = cu[k]; s < cu[k + 1]; ++s) {
+                const double* q = Q + (g * N + s) * d;
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] = lam[g] * M[a * d + b] + kk[a] * v[b];
+                double* o = O + (g * N + s) * d;
+                for (long b = 0; b < d; ++b) {
+                    double acc = 0.0;
+                    for (long a = 0; a < d; ++a) acc += q[a] * M[a * d + b];
+                    o[b] = acc;
+                }
+            }
+        }
+        free(M);
+    }
+}
+
+void lasp2_oracle_bwd_rec_decay(const double* Q, const double* K, const double* V,
+                                const double* dO, double* dQ, double* dK, double* dV,
+                                long G, long N, long d, const long* cu, long n_docs,
+                                const double* lam)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* M = (double*)malloc(sizeof(double) * (size_t)(d * d));
+        for (long k = 0; k < n_docs; ++k) {
+            memset(M, 0, sizeof(double) * (size_t)(d * d));
+            for (long s = cu[k]; s < cu[k + 1]; ++s) {
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                const double* go = dO + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] = lam[g] * M[a * d + b] + kk[a] * v[b];
+                double* dq = dQ + (g * N + s) * d;
+                for (long a = 0; a < d; ++a) {
+                    double acc = 0.0;
+                    for (long b = 0; b < d; ++b) acc += go[b] * M[a * d + b];
+                    dq[a] = acc;
+                }
+            }
+            memset(M, 0, sizeof(double) * (size_t)(d * d));   /* now the adjoint state D */
+            for (long s = cu[k + 1] - 1; s >= cu[k]; --s) {
+                const double* q = Q + (g * N + s) * d;
+                const double* kk = K + (g * N + s) * d;
+                const double* v = V + (g * N + s) * d;
+                const double* go = dO + (g * N + s) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) M[a * d + b] = lam[g] * M[a * d + b] + q[a] * go[b];
+                double* dk = dK + (g * N + s) * d;
+                double* dv = dV + (g * N + s) * d;
+                for (long a = 0; a < d; ++a) {
+                    double acc = 0.0;
+                    for (long b = 0; b < d; ++b) acc += v[b] * M[a * d + b];
+                    dk[a] = acc;
+                }
+                for (long b = 0; b < d; ++b) {
+                    double acc = 0.0;
+                    for (long a = 0; a < d; ++a) acc += kk[a] * M[a * d + b];
+                    dv[b] = acc;
+                }
+            }
+        }
+        free(M);
+    }
+}
+
+/*
+ * Chunked steps with decay, derived from the recurrence over a chunk partition `bounds`
+ * (chunk t = tokens lo_t .. hi_t - 1, n_t = hi_t - lo_t):
+ *   states, anchor_start == 0:  M_t = sum_j lam^(hi_t - 1 - j) k_j^T v_j   (the state as the chunk's
+ *                               last token sees it; the forward's K^T V states)
+ *           anchor_start != 0:  M_t = sum_j lam^(j - lo_t) x_j^T y_j       (the adjoint as the chunk's
+ *                               first token sees it; the backward's Q^T dO states)
+ */
+void lasp2_oracle_chunk_states_decay(const double* X, const double* Y, double* M,
+                                     long G, long N, long d, const long* bounds, long n_chunks,
+                                     const double* lam, int anchor_start)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            double* m = M + (g * n_chunks + t) * d * d;
+            memset(m, 0, sizeof(double) * (size_t)(d * d));
+            for (long j = bounds[t]; j < bounds[t + 1]; ++j) {
+                double w = pow(lam[g], (double)(anchor_start ? j - bounds[t] : bounds[t + 1] - 1 - j));
+                const double* x = X + (g * N + j) * d;
+                const double* y = Y + (g * N + j) * d;
+                for (long a = 0; a < d; ++a)
+                    for (long b = 0; b < d; ++b) m[a * d + b] += w * x[a] * y[b];
+            }
+        }
+    }
+}
+
+/*
+ * Decayed combine of the gathered states (exclusive, restarted at document edges):
+ *   reverse == 0:  P_t = lam^(n_{t-1}) P_{t-1} + M_{t-1}   (M anchored at chunk ends)
+ *   reverse != 0:  P_t = lam^(n_{t+1}) P_{t+1} + M_{t+1}   (M anchored at chunk starts)
+ * so that P_t is the state the last token before chunk t holds (resp. the adjoint the first
+ * token after it holds).
+ */
+void lasp2_oracle_state_prefix_decay(const double* M, double* P, long G, long n_chunks, long d,
+                                     const int* first, int reverse, const long* bounds,
+                                     const double* lam)
+{
+    long dd = d * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        double* run = (double*)malloc(sizeof(double) * (size_t)dd);
+        memset(run, 0, sizeof(double) * (size_t)dd);
+        for (long u = 0; u < n_chunks; ++u) {
+            long t = reverse ? n_chunks - 1 - u : u;
+            int edge = reverse ? (t == n_chunks - 1 || (first && first[t + 1]))
+                               : (t == 0 || (first && first[t]));
+            if (edge) memset(run, 0, sizeof(double) * (size_t)dd);
+            const double* m = M + (g * n_chunks + t) * dd;
+            double* p = P + (g * n_chunks + t) * dd;
+            double w = pow(lam[g], (double)(bounds[t + 1] - bounds[t]));
+            for (long e = 0; e < dd; ++e) { double add = m[e]; p[e] = run[e]; run[e] = w * run[e] + add; }
+        }
+        free(run);
+    }
+}
+
+/*
+ * Forward per chunk with decay: for the token at local index a of chunk t,
+ *   o = sum_{b<=a} lam^(a-b) (q_a.k_b) v_b  +  lam^(a+1) q_a P_t .
+ */
+void lasp2_oracle_attn_fwd_chunked_decay(const double* Q, const double* K, const double* V,
+                                         const double* P, double* O, long G, long N, long d,
+                                         const long* bounds, long n_chunks, const double* lam)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            long lo = bounds[t], hi = bounds[t + 1];
+            const double* p = P + (g * n_chunks + t) * d * d;
+            for (long i = lo; i < hi; ++i) {
+                const double* q = Q + (g * N + i) * d;
+                double* o = O + (g * N + i) * d;
+                double wi = pow(lam[g], (double)(i - lo + 1));
+                for (long b = 0; b < d; ++b) {
+                    double inter = 0.0;
+                    for (long a = 0; a < d; ++a) inter += q[a] * p[a * d + b];
+                    o[b] = wi * inter;
+                }
+                for (long j = lo; j <= i; ++j) {
+                    double s = pow(lam[g], (double)(i - j)) * dot(q, K + (g * N + j) * d, d);
+                    for (long b = 0; b < d; ++b) o[b] += s * V[(g * N + j) * d + b];
+                }
+            }
+        }
+    }
+}
+
+/*
+ * Backward per chunk with decay, from the cached prefix P_t and the decayed suffix dP_t:
+ *   dq_a = sum_{b<=a} lam^(a-b) (dO_a.v_b) k_b + lam^(a+1) dO_a P_t^T
+ *   dk_b = sum_{a>=b} lam^(a-b) (dO_a.v_b) q_a + lam^(n-b) v_b dP_t^T
+ *   dv_b = sum_{a>=b} lam^(a-b) (q_a.k_b) dO_a + lam^(n-b) k_b dP_t
+ * (n = chunk length; lam^(n-b) carries the adjoint from the first token after the chunk).
+ */
+void lasp2_oracle_attn_bwd_chunked_decay(const double* Q, const double* K, const double* V,
+                                         const double* dO, const double* P, const double* dP,
+                                         double* dQ, double* dK, double* dV, long G, long N, long d,
+                                         const long* bounds, long n_chunks, const double* lam)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        for (long t = 0; t < n_chunks; ++t) {
+            long lo = bounds[t], hi = bounds[t + 1];
+            const double* p = P + (g * n_chunks + t) * d * d;
+            const double* dp = dP + (g * n_chunks + t) * d * d;
+            for (long i = lo; i < hi; ++i) {
+                const double* go = dO + (g * N + i) * d;
+                double* dq = dQ + (g * N + i) * d;
+                double wi = pow(lam[g], (double)(i - lo + 1));
+                for (long a = 0; a < d; ++a) {
+                    double inter = 0.0;
+                    for (long b = 0; b < d; ++b) inter += go[b] * p[a * d + b];
+                    dq[a] = wi * inter;
+                }
+                for (long j = lo; j <= i; ++j) {
+                    double gij = pow(lam[g], (double)(i - j)) * dot(go, V + (g * N + j) * d, d);
+                    for (long a = 0; a < d; ++a) dq[a] += gij * K[(g * N + j) * d + a];
+                }
+            }
+            for (long j = lo; j < hi; ++j) {
+                const double* kk = K + (g * N + j) * d;
+                const double* v = V + (g * N + j) * d;
+                double* dk = dK + (g * N + j) * d;
+                double* dv = dV + (g * N + j) * d;
+                double wj = pow(lam[g], (double)(hi - j));
+                for (long a = 0; a < d; ++a) {
+                    double inter = 0.0;
+                    for (long b = 0; b < d; ++b) inter += v[b] * dp[a * d + b];
+                    dk[a] = wj * inter;
+                }
+                for (long b = 0; b < d; ++b) {
+                    double inter = 0.0;
+                    for (long a = 0; a < d; ++a) inter += kk[a] * dp[a * d + b];
+                    dv[b] = wj * inter;
+                }
+                for (long i = j; i < hi; ++i) {
+                    double w = pow(lam[g], (double)(i - j));
+                    double gij = w * dot(dO + (g * N + i) * d, v, d);
+                    double sij = w * dot(Q + (g * N + i) * d, kk, d);
+                    for (long a = 0; a < d; ++a) {
+                        dk[a] += gij * Q[(g * N + i) * d + a];
+                        dv[a] += sij * dO[(g * N + i) * d + a];
+                    }
+                }
+            }
+        }
+    }
 }
