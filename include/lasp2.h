@@ -31,6 +31,19 @@
  * No state crosses a document boundary (paper appendix "Variable Length",
  * read as a block-diagonal causal mask).  Ragged last chunks/slots are fine.
  *
+ * Scalar decay (optional; the Retention / Lightning Attention form of the
+ * layers in the paper's Table 2, for which it prints no formulas).  With a
+ * per-head factor lam in (0, 1] the mask entry Psi_ij = 1 becomes lam^(i-j):
+ *     o_s = sum_{i<=s} lam^(s-i) (q_s . k_i) v_i ,
+ * i.e. the recurrence M_s = lam M_{s-1} + k_s^T v_s, o_s = q_s M_s.  The steps
+ * keep their shape with decayed weights: a slot's state is taken as its last
+ * token sees it, M_t = sum_j lam^(end_t - j) k_j^T v_j; the combine carries
+ * the slot lengths, P_t = lam^(n_{t-1}) P_{t-1} + M_{t-1}; the token at local
+ * index a of a chunk reads the state before the chunk with weight lam^(a+1).
+ * The backward mirrors this with states anchored at the slots' first tokens.
+ * lam = 1 for every head gives exactly the undecayed path.  Decay is given by
+ * the two `decay_*` pointers of the descriptor (both NULL: none).
+ *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers, 16-byte aligned, contiguous,
  *     d fastest: Q,K,V,O,dO,dQ,dK,dV are [B,H,N,d] in `dtype` (fp32 or bf16);
@@ -50,8 +63,9 @@
  *     and launches nothing (pointers are then not examined).
  *   - Supported: d in {16, 32, 64, 128}; 1 <= C <= 512.  The MFMA kernels
  *     cover bf16 with d = 128 for every C (they tile a slot in chunks of
- *     their own, which the result does not depend on); any other supported
- *     combination runs the plain fp32-FMA kernels.  There is no CPU fallback.
+ *     their own, which the result does not depend on) without decay; any
+ *     other supported combination runs the plain fp32-FMA kernels.  There is
+ *     no CPU fallback.
  */
 #ifndef LASP2_H
 #define LASP2_H
@@ -73,7 +87,10 @@ typedef enum {
                                    increasing, or only one of the two cu pointers given */
     LASP2_ERR_WORKSPACE = -5,   /* workspace smaller than lasp2_workspace_size()        */
     LASP2_ERR_ALIGN = -6,       /* a device pointer is not 16-byte aligned              */
-    LASP2_ERR_LAUNCH = -7       /* the HIP runtime reported an error at launch          */
+    LASP2_ERR_LAUNCH = -7,      /* the HIP runtime reported an error at launch          */
+    LASP2_ERR_DECAY = -8        /* only one of the two decay pointers given, a factor
+                                   outside (0, 1], or decay passed to an entry point
+                                   without masking                                      */
 } lasp2_status_t;
 
 typedef enum { LASP2_F32 = 0, LASP2_BF16 = 1 } lasp2_dtype_t;
@@ -86,6 +103,8 @@ typedef struct lasp2_desc {
     int32_t n_seqs;                  /* packed: number of documents (>= 1); 0 => not packed      */
     const int32_t* cu_seqlens_host;  /* HOST  ptr, n_seqs+1 offsets, cu[0]=0 < ... < cu[n]=N     */
     const int32_t* cu_seqlens_dev;   /* DEVICE ptr holding the same n_seqs+1 values              */
+    const float* decay_host;         /* HOST  ptr, H per-head decay factors in (0, 1]; NULL => none */
+    const float* decay_dev;          /* DEVICE ptr holding the same H values (NULL iff host is)  */
 } lasp2_desc_t;
 
 /* Number of state slots T_s per (b,h) for this descriptor (see "Slots" above). */
@@ -100,6 +119,9 @@ int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
  * one state per slot: M[b,h,s] = sum over the slot's tokens of k^T v (fp32).
  * With (Q, dO) in place of (K, V) it yields dM_t = Q_t^T dO_t of the backward.
  * In:  K, V [B,H,N,d] (device, `dtype`).   Out: M [B,H,T_s,d,d] fp32 (device).
+ * With decay the sum carries the weights lam^(end of slot - token), the state
+ * as the slot's last token sees it (the backward computes its own states,
+ * anchored at the slots' first tokens, internally).
  */
 int lasp2_chunk_states(const lasp2_desc_t* desc, const void* K, const void* V,
                        float* M, void* stream);
@@ -109,6 +131,9 @@ int lasp2_chunk_states(const lasp2_desc_t* desc, const void* K, const void* V,
  * AllGather + SuffixSum (backward): exclusive, restarted at document edges.
  *   reverse == 0:  P[s] = sum_{r<s, same doc} M[r]   (M_{1:t-1};  first = 0)
  *   reverse != 0:  P[s] = sum_{r>s, same doc} M[r]   (dM_{t+1:T}; last  = 0)
+ * With decay: P[s] = lam^(n_r) P[r] + M[r] for the neighbouring slot r = s-1
+ * (reverse: r = s+1) of n_r tokens; M is then expected anchored at slot ends
+ * (reverse: at slot starts).
  * In: M [B,H,T_s,d,d] fp32.  Out: P same shape; P may alias M exactly
  * (in place); partial overlap is not allowed.
  */

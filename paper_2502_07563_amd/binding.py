@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "liblasp2.so")
 LASP2_F32, LASP2_BF16 = 0, 1
 STATUS = {0: "LASP2_OK", -1: "LASP2_ERR_NULL", -2: "LASP2_ERR_SHAPE", -3: "LASP2_ERR_DTYPE",
           -4: "LASP2_ERR_SEQLENS", -5: "LASP2_ERR_WORKSPACE", -6: "LASP2_ERR_ALIGN",
-          -7: "LASP2_ERR_LAUNCH"}
+          -7: "LASP2_ERR_LAUNCH", -8: "LASP2_ERR_DECAY"}
 
 
 class Desc(ctypes.Structure):
@@ -25,7 +25,8 @@ class Desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("C", ctypes.c_int32), ("L", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
-                ("cu_seqlens_host", ctypes.c_void_p), ("cu_seqlens_dev", ctypes.c_void_p)]
+                ("cu_seqlens_host", ctypes.c_void_p), ("cu_seqlens_dev", ctypes.c_void_p),
+                ("decay_host", ctypes.c_void_p), ("decay_dev", ctypes.c_void_p)]
 
 
 class Lasp2Error(RuntimeError):
@@ -73,13 +74,13 @@ def status_string(code: int) -> str:
 class Problem:
     """A descriptor plus the host/device copies of the packed-sequence offsets it points to."""
 
-    def __init__(self, B, H, N, d, C, L=0, dtype="bf16", cu_seqlens=None, device="cuda"):
+    def __init__(self, B, H, N, d, C, L=0, dtype="bf16", cu_seqlens=None, device="cuda", decay=None):
         self.B, self.H, self.N, self.d, self.C, self.L = B, H, N, d, C, L
         self.dtype = dtype
         self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
         self.desc = Desc(B=B, H=H, N=N, d=d, C=C, L=L,
                          dtype={"f32": LASP2_F32, "bf16": LASP2_BF16}[dtype], n_seqs=0,
-                         cu_seqlens_host=None, cu_seqlens_dev=None)
+                         cu_seqlens_host=None, cu_seqlens_dev=None, decay_host=None, decay_dev=None)
         self._cu_host = self._cu_dev = None
         if cu_seqlens is not None:
             self._cu_host = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
@@ -87,6 +88,13 @@ class Problem:
             self.desc.n_seqs = len(self._cu_host) - 1
             self.desc.cu_seqlens_host = self._cu_host.ctypes.data
             self.desc.cu_seqlens_dev = self._cu_dev.data_ptr()
+
+        self._decay_host = self._decay_dev = None
+        if decay is not None:      # one factor per head
+            self._decay_host = np.ascontiguousarray(np.broadcast_to(np.asarray(decay, dtype=np.float32), (H,)))
+            self._decay_dev = torch.from_numpy(self._decay_host.copy()).to(device)
+            self.desc.decay_host = self._decay_host.ctypes.data
+            self.desc.decay_dev = self._decay_dev.data_ptr()
 
     @property
     def ref(self):

@@ -24,7 +24,7 @@ __device__ __forceinline__ void st(__hip_bfloat16* p, float v) { *p = __float2bf
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void states_generic_kernel(Geom g, const T* __restrict__ K,
                                                                   const T* __restrict__ V,
-                                                                  float* __restrict__ M)
+                                                                  float* __restrict__ M, int anchor_start)
 {
     constexpr int TM = D / 16;
     const int s = blockIdx.x, grp = blockIdx.y;
@@ -39,12 +39,15 @@ __global__ __launch_bounds__(kThreads) void states_generic_kernel(Geom g, const 
 #pragma unroll
         for (int j = 0; j < TM; ++j) acc[i][j] = 0.f;
 
+    const float l2 = decay_log2(g, grp);
     for (int t = 0; t < len; ++t) {
         const T* kr = K + gbase + (size_t)(tok0 + t) * D;
         const T* vr = V + gbase + (size_t)(tok0 + t) * D;
+        // decay: the token's weight as seen from the slot's last (or first) token
+        const float wt = exp2f((float)(anchor_start ? t : len - 1 - t) * l2);
         float kk[TM], vv[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) kk[i] = ld(kr + ty + 16 * i);
+        for (int i = 0; i < TM; ++i) kk[i] = wt * ld(kr + ty + 16 * i);
 #pragma unroll
         for (int j = 0; j < TM; ++j) vv[j] = ld(vr + tx + 16 * j);
 #pragma unroll
@@ -87,6 +90,8 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
     }
     __syncthreads();
 
+    // decay: lam^e = exp2f(e * l2); l2 = 0 without decay, and every weight is then exactly 1
+    const float l2 = decay_log2(g, grp);
     const int nch = (len + g.C - 1) / g.C;
     for (int ci = 0; ci < nch; ++ci) {
         const int c = reverse ? nch - 1 - ci : ci;
@@ -109,6 +114,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
                 if (keep) {
                     const T* br = Bk + gbase + (size_t)(c0 + j) * D;
                     for (int a = 0; a < D; ++a) acc = fmaf(Ablk[r * AS + a], ld(br + a), acc);
+                    acc *= exp2f((float)(reverse ? j - i : i - j) * l2);
                 }
                 S[r * SS + j] = acc;
             }
@@ -123,14 +129,19 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
                 for (int j = jlo; j <= jhi; ++j)
                     intra = fmaf(S[r * SS + j], ld(Cv + gbase + (size_t)(c0 + j) * D + b), intra);
                 for (int a = 0; a < D; ++a) inter = fmaf(Ablk[r * AS + a], Mst[a * D + b], inter);
-                st(out + gbase + (size_t)(c0 + i) * D + b, intra + inter);
+                // the state sits one token before the chunk (causal) or one after it (anti-causal)
+                const float wi = exp2f((float)(reverse ? clen - i : i + 1) * l2);
+                st(out + gbase + (size_t)(c0 + i) * D + b, fmaf(wi, inter, intra));
             }
             __syncthreads();
         }
 
         if (ci + 1 < nch) {
-            // running state += Bk_c^T Cv_c ; each thread owns its own elements
+            // running state = lam^clen * state + sum_t w_t Bk_t^T Cv_t, w_t = the token's weight as
+            // seen from the chunk's last (causal) or first (anti-causal) token; each thread owns
+            // its own elements
             const int ty = tid / 16, tx = tid % 16;
+            const float wc = exp2f((float)clen * l2);
             float acc[TM][TM];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -139,9 +150,10 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
             for (int t = 0; t < clen; ++t) {
                 const T* br = Bk + gbase + (size_t)(c0 + t) * D;
                 const T* cr = Cv + gbase + (size_t)(c0 + t) * D;
+                const float wt = exp2f((float)(reverse ? t : clen - 1 - t) * l2);
                 float bb[TM], cc[TM];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) bb[i] = ld(br + ty + 16 * i);
+                for (int i = 0; i < TM; ++i) bb[i] = wt * ld(br + ty + 16 * i);
 #pragma unroll
                 for (int j = 0; j < TM; ++j) cc[j] = ld(cr + tx + 16 * j);
 #pragma unroll
@@ -152,7 +164,10 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TM; ++j) Mst[(ty + 16 * i) * D + tx + 16 * j] += acc[i][j];
+                for (int j = 0; j < TM; ++j) {
+                    float& m = Mst[(ty + 16 * i) * D + tx + 16 * j];
+                    m = fmaf(wc, m, acc[i][j]);
+                }
             __syncthreads();
         }
     }
@@ -172,6 +187,7 @@ __global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const fl
     if (e >= dd) return;
     const size_t base = (size_t)blockIdx.y * (size_t)g.T_s * dd + e;
     const int ndocs = g.n_seqs ? g.n_seqs : 1;
+    const float l2 = decay_log2(g, blockIdx.y);
     const int step = reverse ? -1 : 1;
     int s = reverse ? g.T_s - 1 : 0;
     for (int kk = 0; kk < ndocs; ++kk) {
@@ -190,7 +206,13 @@ __global__ __launch_bounds__(kThreads) void state_prefix_kernel(Geom g, const fl
                 if (r + u < ns) {
                     float4* dst = reinterpret_cast<float4*>(P + base + (size_t)(s + step * u) * dd);
                     if (!inclusive) *dst = run;
-                    run.x += m[u].x; run.y += m[u].y; run.z += m[u].z; run.w += m[u].w;
+                    // decay: the carried state ages by the length of the slot it crosses
+                    // (slot index inside the document: r+u counted from the walk's start)
+                    const int idx = reverse ? ns - 1 - (r + u) : r + u;
+                    const int n = (int)min((int64_t)g.L, (int64_t)dlen - (int64_t)idx * g.L);
+                    const float w = exp2f((float)n * l2);
+                    run.x = fmaf(w, run.x, m[u].x); run.y = fmaf(w, run.y, m[u].y);
+                    run.z = fmaf(w, run.z, m[u].z); run.w = fmaf(w, run.w, m[u].w);
                     if (inclusive) *dst = run;
                 }
             s += step * min(kScanBatch, ns - r);
@@ -300,14 +322,14 @@ hipError_t rows_state_generic_T(const Geom& g, const T* A, const float* state, T
 }
 
 template <typename T>
-hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, hipStream_t st)
+hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, int anchor, hipStream_t st)
 {
     dim3 grid(g.T_s, g.G), block(kThreads);
     switch (g.d) {
-        case 16: hipLaunchKernelGGL((states_generic_kernel<T, 16>), grid, block, 0, st, g, K, V, M); break;
-        case 32: hipLaunchKernelGGL((states_generic_kernel<T, 32>), grid, block, 0, st, g, K, V, M); break;
-        case 64: hipLaunchKernelGGL((states_generic_kernel<T, 64>), grid, block, 0, st, g, K, V, M); break;
-        default: hipLaunchKernelGGL((states_generic_kernel<T, 128>), grid, block, 0, st, g, K, V, M); break;
+        case 16: hipLaunchKernelGGL((states_generic_kernel<T, 16>), grid, block, 0, st, g, K, V, M, anchor); break;
+        case 32: hipLaunchKernelGGL((states_generic_kernel<T, 32>), grid, block, 0, st, g, K, V, M, anchor); break;
+        case 64: hipLaunchKernelGGL((states_generic_kernel<T, 64>), grid, block, 0, st, g, K, V, M, anchor); break;
+        default: hipLaunchKernelGGL((states_generic_kernel<T, 128>), grid, block, 0, st, g, K, V, M, anchor); break;
     }
     return hipGetLastError();
 }
@@ -343,12 +365,13 @@ hipError_t attn_generic_T(const Geom& g, const T* A, const T* Bk, const T* Cv, c
 }  // namespace
 
 hipError_t launch_states_generic(const Geom& g, int dtype, const void* K, const void* V, float* M,
-                                 hipStream_t st)
+                                 int anchor_start, hipStream_t st)
 {
     if (dtype == LASP2_F32)
-        return states_generic_T(g, static_cast<const float*>(K), static_cast<const float*>(V), M, st);
+        return states_generic_T(g, static_cast<const float*>(K), static_cast<const float*>(V), M,
+                                anchor_start, st);
     return states_generic_T(g, static_cast<const __hip_bfloat16*>(K),
-                            static_cast<const __hip_bfloat16*>(V), M, st);
+                            static_cast<const __hip_bfloat16*>(V), M, anchor_start, st);
 }
 
 hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const void* Bk,

@@ -882,8 +882,8 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
 bool mfma_path_supported(const Geom& g, int dtype)
 {
     // The kernels tile a slot in their own chunks (the result does not depend on the chunk
-    // length), so every C of the caller is served.
-    return dtype == LASP2_BF16 && g.d == D;
+    // length), so every C of the caller is served.  They implement the undecayed mask only.
+    return dtype == LASP2_BF16 && g.d == D && g.decay == nullptr;
 }
 
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M, hipStream_t st)

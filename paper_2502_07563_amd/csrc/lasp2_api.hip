@@ -51,7 +51,19 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     // one-dimensional grids carry up to three workgroups per (group, slot) pair
     if (G * T_s > (int64_t)(INT32_MAX / 4)) return LASP2_ERR_SHAPE;
 
+    // decay: both pointers or neither; every factor in (0, 1]
+    if ((desc->decay_host == nullptr) != (desc->decay_dev == nullptr)) return LASP2_ERR_DECAY;
+    if (desc->decay_host) {
+        for (int h = 0; h < desc->H; ++h) {
+            const float lam = desc->decay_host[h];
+            if (!(lam > 0.f && lam <= 1.f)) return LASP2_ERR_DECAY;
+        }
+        if (reinterpret_cast<uintptr_t>(desc->decay_dev) & 3u) return LASP2_ERR_ALIGN;
+    }
+
     g->G = (int32_t)G;
+    g->H = desc->H > 0 ? desc->H : 1;
+    g->decay = desc->decay_dev;
     g->N = desc->N;
     g->d = desc->d;
     g->C = desc->C;
@@ -74,11 +86,12 @@ int check_ptrs(std::initializer_list<const void*> ptrs)
 
 int from_hip(hipError_t e) { return e == hipSuccess ? LASP2_OK : LASP2_ERR_LAUNCH; }
 
+// anchor_start matters with decay only: states as the slot's first token sees them (backward)
 hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, float* M,
-                      hipStream_t st)
+                      int anchor_start, hipStream_t st)
 {
     if (mfma_path_supported(g, dtype)) return launch_states_mfma(g, K, V, M, st);
-    return launch_states_generic(g, dtype, K, V, M, st);
+    return launch_states_generic(g, dtype, K, V, M, anchor_start, st);
 }
 
 }  // namespace
@@ -120,7 +133,7 @@ int lasp2_chunk_states(const lasp2_desc_t* desc, const void* K, const void* V, f
     if (empty) return LASP2_OK;
     rc = check_ptrs({K, V, M});
     if (rc != LASP2_OK) return rc;
-    return from_hip(run_states(g, desc->dtype, K, V, M, (hipStream_t)stream));
+    return from_hip(run_states(g, desc->dtype, K, V, M, 0, (hipStream_t)stream));
 }
 
 int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P, int reverse,
@@ -171,7 +184,7 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     // dM_t = Q_t^T dO_t per slot, then its suffix combine in place: exclusive for the plain
     // kernels (which walk each slot backwards), inclusive for the MFMA kernels (which walk
     // forwards and subtract, see attn_mfma_kernel).
-    hipError_t e = run_states(g, desc->dtype, Q, dO, dR, st);
+    hipError_t e = run_states(g, desc->dtype, Q, dO, dR, 1, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     e = launch_state_prefix(g, dR, dR, 1, fast ? 1 : 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
@@ -194,6 +207,7 @@ int lasp2_state_total(const lasp2_desc_t* desc, const float* M, float* S, void* 
     bool empty = false;
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
+    if (g.decay) return LASP2_ERR_DECAY;   // decay is defined for the masked path only
     if (empty) return LASP2_OK;
     rc = check_ptrs({M, S});
     if (rc != LASP2_OK) return rc;
@@ -206,6 +220,7 @@ int lasp2_nomask_fwd(const lasp2_desc_t* desc, const void* Q, const float* S, vo
     bool empty = false;
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
+    if (g.decay) return LASP2_ERR_DECAY;   // decay is defined for the masked path only
     if (empty) return LASP2_OK;
     rc = check_ptrs({Q, S, O});
     if (rc != LASP2_OK) return rc;
@@ -225,6 +240,7 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, con
     bool empty = false;
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
+    if (g.decay) return LASP2_ERR_DECAY;   // decay is defined for the masked path only
     if (empty) return LASP2_OK;
     rc = check_ptrs({Q, K, V, dO, S, dQ, dK, dV, workspace});
     if (rc != LASP2_OK) return rc;
@@ -234,7 +250,7 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, con
     hipStream_t st = (hipStream_t)stream;
     float* dS = static_cast<float*>(workspace);
     // dM_t = Q_t^T dO_t per slot, then the sum over the document's slots in place
-    hipError_t e = run_states(g, desc->dtype, Q, dO, dS, st);
+    hipError_t e = run_states(g, desc->dtype, Q, dO, dS, 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     e = launch_state_total(g, dS, dS, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
@@ -260,6 +276,7 @@ const char* lasp2_status_string(int status)
         case LASP2_ERR_WORKSPACE: return "workspace too small";
         case LASP2_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case LASP2_ERR_LAUNCH: return "HIP launch failed";
+        case LASP2_ERR_DECAY: return "invalid decay factors, or decay given to an entry point without masking";
         default: return "unknown status";
     }
 }

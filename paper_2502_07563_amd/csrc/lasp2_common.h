@@ -19,7 +19,15 @@ struct Geom {
     int32_t T_s;          // slots per group
     int32_t n_seqs;       // packed: number of documents; 0 = not packed
     const int32_t* cu;    // packed: DEVICE pointer to n_seqs+1 offsets
+    int32_t H;            // heads (group g uses decay[g % H])
+    const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
 };
+
+// log2 of the decay factor of group grp (0 when there is no decay): lam^e = exp2f(e * log2 lam).
+__device__ __forceinline__ float decay_log2(const Geom& g, int grp)
+{
+    return g.decay ? log2f(g.decay[grp % g.H]) : 0.f;
+}
 
 // Token range [tok0, tok0+len) of slot s.  Unpacked: direct.  Packed: walk the
 // documents (uniform scalar loads; n_seqs is small next to the work per slot).
@@ -54,8 +62,9 @@ __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int&
 // ---- launchers implemented in the kernel files (return hipGetLastError()) ----
 
 // Plain fp32-FMA kernels, any supported (dtype, d, C).
+// anchor_start (decay only): weights lam^(token - slot start) instead of lam^(slot end - token).
 hipError_t launch_states_generic(const Geom& g, int dtype, const void* K, const void* V,
-                                 float* M, hipStream_t st);
+                                 float* M, int anchor_start, hipStream_t st);
 // out = [(A Bk^T) (.) mask] Cv + A * state, state += Bk^T Cv chunk by chunk.
 //   reverse = 0: causal mask, chunks walked first to last, state = prefix;
 //   reverse = 1: anti-causal mask (j >= i), chunks walked last to first, state = suffix.

@@ -40,7 +40,7 @@ def test_header_symbols_are_exported():
 
 
 def test_status_strings():
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert B.status_string(code) and B.status_string(code) != "unknown status"
     assert B.status_string(-99) == "unknown status"
 
@@ -119,6 +119,23 @@ def test_null_and_alignment_errors_reach_no_device():
         a = list(args); a[i] = None
         assert lib.lasp2_nomask_bwd(r, *a, ctypes.c_size_t(1 << 40), None) == -1
     assert lib.lasp2_nomask_bwd(r, *args, ctypes.c_size_t(need.value - 1), None) == -5
+
+
+def test_decay_errors():
+    lam = np.array([0.9, 1.0], dtype=np.float32)
+    assert _slots(_desc(decay_host=lam.ctypes.data, decay_dev=0x3000))[0] == 0
+    assert _slots(_desc(decay_host=lam.ctypes.data))[0] == -8            # device copy missing
+    assert _slots(_desc(decay_dev=0x3000))[0] == -8                      # host copy missing
+    assert _slots(_desc(decay_host=lam.ctypes.data, decay_dev=0x3002))[0] == -6
+    for bad in (0.0, -0.5, 1.5, float("nan")):
+        b = np.array([0.9, bad], dtype=np.float32)
+        assert _slots(_desc(decay_host=b.ctypes.data, decay_dev=0x3000))[0] == -8
+    # decay is defined for the masked path only
+    lib = B.lib()
+    r = ctypes.byref(_desc(decay_host=lam.ctypes.data, decay_dev=0x3000))
+    assert lib.lasp2_state_total(r, FAKE, FAKE, None) == -8
+    assert lib.lasp2_nomask_fwd(r, FAKE, FAKE, FAKE, None) == -8
+    assert lib.lasp2_nomask_bwd(r, *([FAKE] * 9), ctypes.c_size_t(1 << 40), None) == -8
 
 
 def test_empty_problem_is_ok_without_pointers():

@@ -1,0 +1,94 @@
+"""GPU parity of the masked entry points with scalar decay (mask entries lam^(i-j), one factor
+per head) against the CPU oracle's decayed definition, element by element, on seeded inputs:
+fp32 and bf16 storage, several chunks and slots, ragged tails, packed documents, and the
+lam = 1 case, which must reproduce the undecayed path bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2502_07563_amd import synth
+from tests.util import TOL, TOL_STATE, host_inputs, rel_l2, slot_partition, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _lams(H, seed):
+    """Per-head factors in the range of the Retention / Lightning Attention schedules, plus a
+    strongly decaying head and an undecayed one."""
+    base = 1.0 - 2.0 ** (-5.0 - np.arange(H))
+    extra = np.array([0.5, 1.0, 0.9])
+    lam = np.where(np.arange(H) % 3 == 0, base, extra[np.arange(H) % 3])
+    return lam.astype(np.float32)
+
+
+def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None, lam=None):
+    import torch
+    from paper_2502_07563_amd import binding as bd
+
+    G = B * H
+    lam = _lams(H, seed) if lam is None else np.asarray(lam, dtype=np.float32)
+    lam_g = np.tile(lam.astype(np.float64), B)          # group g = b*H + h
+    x = host_inputs(seed, G, N, d, dtype)
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu, decay=lam)
+    bounds, first = slot_partition(N, L if L else C, cu)
+    Q, K, V, dO = (to_device(x[n], B, H, dtype) for n in ("Q", "K", "V", "dO"))
+    M = bd.alloc_states(p)
+    P = torch.empty_like(M)
+    O = torch.full_like(Q, float("nan"))
+    bd.lasp2_chunk_states(p, K, V, M)
+    bd.lasp2_state_prefix(p, M, P, False)
+    bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+    dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+    ws = torch.empty_like(M)
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
+    torch.cuda.synchronize()
+
+    x64 = {k: v.astype(np.float64) for k, v in x.items()}
+    errs = {}
+    M_ref = oracle.chunk_states_decay(x64["K"], x64["V"], bounds, lam_g)
+    P_ref = oracle.state_prefix_decay(M_ref, bounds, lam_g, first)
+    dP_ref = oracle.state_prefix_decay(oracle.chunk_states_decay(x64["Q"], x64["dO"], bounds, lam_g, anchor_start=True),
+                                       bounds, lam_g, first, reverse=True)
+    errs["M"] = rel_l2(to_host(M), M_ref)
+    errs["P"] = rel_l2(to_host(P), P_ref)
+    errs["dP"] = rel_l2(to_host(ws), dP_ref)        # the generic path leaves the exclusive suffix there
+    errs["O"] = rel_l2(to_host(O), oracle.fwd_def_decay(x64["Q"], x64["K"], x64["V"], lam_g, cu))
+    refs = oracle.bwd_def_decay(x64["Q"], x64["K"], x64["V"], x64["dO"], lam_g, cu)
+    for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs):
+        errs[name] = rel_l2(to_host(got), ref)
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs["M"], errs["P"], errs["dP"]) <= TOL_STATE, errs
+    for k in ("O", "dQ", "dK", "dV"):
+        assert errs[k] <= TOL[dtype], errs
+    return dict(O=O, dQ=dQ, dK=dK, dV=dV, P=P)
+
+
+@pytest.mark.parametrize("N,d,C,L", [(1024, 64, 128, 0), (1000, 32, 128, 256), (777, 16, 50, 150),
+                                     (5, 16, 1, 2), (1, 16, 8, 0), (130, 128, 64, 128)])
+def test_fp32_shapes(oracle, N, d, C, L):
+    _run(oracle, 2, 3, N, d, C, L, "f32", seed=90 + N)
+
+
+@pytest.mark.parametrize("N,d,C,L", [(1024, 128, 256, 512), (900, 64, 128, 256), (300, 128, 64, 0)])
+def test_bf16_shapes(oracle, N, d, C, L):
+    _run(oracle, 1, 3, N, d, C, L, "bf16", seed=110 + N)
+
+
+@pytest.mark.parametrize("dtype,d,C,L", [("f32", 32, 64, 128), ("bf16", 128, 128, 256)])
+def test_packed_documents(oracle, dtype, d, C, L):
+    cu = synth.doc_offsets(6, 1536, 7, mean_len=1536 / 7, min_len=1)
+    _run(oracle, 1, 3, 1536, d, C, L, dtype, seed=120, cu=cu)
+
+
+def test_all_ones_decay_is_bit_identical_to_no_decay(oracle):
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    B, H, N, d, C, L = 1, 2, 600, 32, 64, 128
+    with_decay = _run(oracle, B, H, N, d, C, L, "f32", seed=130, lam=np.ones(H))
+    x = host_inputs(130, B * H, N, d, "f32")
+    p = bd.Problem(B, H, N, d, C, L, "f32")
+    Q, K, V, dO = (to_device(x[n], B, H, "f32") for n in ("Q", "K", "V", "dO"))
+    O, P = bd.forward(p, Q, K, V)
+    dQ, dK, dV, _ = bd.backward(p, Q, K, V, dO, P)
+    torch.cuda.synchronize()
+    for name, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV), ("P", P)):
+        assert torch.equal(t, with_decay[name]), name
