@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--slot-len", type=int, default=None,
                     help="tokens per state slot L (a multiple of C) instead of the workload's own; "
                          "L = N is the serial-carry schedule with one slot per head")
+    ap.add_argument("--decay", action="store_true",
+                    help="run the step with scalar decay, per-head factors 1 - 2^(-5-h) (not the headline "
+                         "workload; the CPU baseline, which is the undecayed oracle, is then left out)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -87,7 +90,11 @@ def main():
     cu = synth.config_offsets(cfg)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    p = bd.Problem(B, H, N, d, C, L, dtype, cu)
+    decay = None
+    if args.decay:
+        import numpy as np
+        decay = (1.0 - 2.0 ** (-5.0 - np.arange(H))).astype(np.float32)
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu, decay=decay)
     tdt = p.torch_dtype
 
     gen = torch.Generator(device=dev)
@@ -166,7 +173,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={B} H={H} N={N} d={d} C={C} L={L or C}"
-                               + (f" packed {cfg['n_docs']} docs" if cu is not None else ""),
+                               + (f" packed {cfg['n_docs']} docs" if cu is not None else "")
+                               + (" decay 1-2^(-5-h)" if args.decay else ""),
                    "state_slots": int(T_s)},
         "ms": {"chunk_states": seg[0], "state_prefix": seg[1], "attn_fwd": seg[2], "attn_bwd": seg[3]},
         "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
@@ -176,7 +184,10 @@ def main():
                      "avg_launch_ms": avg_ms, "fwd_launch_ms": t_fwd, "bwd_launch_ms": t_bwd,
                      "fwd_launch_GBps": bytes_fwd / (t_fwd * 1e-3) / 1e9},
     }
-    if not args.no_cpu_baseline:
+    if args.decay:
+        out["roofline"]["kernel"] = "attn_decay_mfma_kernel, average of its two launches per step"
+        out["roofline"]["traffic"] = None
+    if not args.no_cpu_baseline and not args.decay:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
     print(json.dumps(out))
 

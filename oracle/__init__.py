@@ -409,3 +409,22 @@ def backward_by_algorithm_decay(Q, K, V, dO, bounds, lam, first=None):
     dM = chunk_states_decay(Q, dO, bounds, lam, anchor_start=True)
     dP = state_prefix_decay(dM, bounds, lam, first, reverse=True)
     return attn_bwd_chunked_decay(Q, K, V, dO, P, dP, bounds, lam) + (dM, dP)
+
+
+def def_rows_decay(Q, K, V, dO, rows, which, lam, cu=None):
+    """Rows `rows` of O (which=0), dQ (1), dK (2) or dV (3) of the decayed definition, ONE group."""
+    N, d = Q.shape
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    if dO is None:
+        assert which == 0
+        g = None
+    else:
+        dO, g = _d(dO)
+    rows, r = _l(rows)
+    out = np.empty((len(rows), d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_def_rows_decay(q, k, v, g, ctypes.c_long(N), ctypes.c_long(d), c,
+                                       ctypes.c_long(len(cu) - 1), r, ctypes.c_long(len(rows)),
+                                       ctypes.c_int(which), ctypes.c_double(float(lam)),
+                                       out.ctypes.data_as(_c_dp))
+    return out

@@ -879,3 +879,37 @@ void lasp2_oracle_attn_bwd_chunked_decay(const double* Q, const double* K, const
         }
     }
 }
+
+/*
+ * Selected rows of the decayed definition (one group; Q,K,V,dO are [N][d]; lam is that group's
+ * factor).  which: 0 -> O rows, 1 -> dQ rows, 2 -> dK rows, 3 -> dV rows.
+ */
+void lasp2_oracle_def_rows_decay(const double* Q, const double* K, const double* V,
+                                 const double* dO, long N, long d, const long* cu, long n_docs,
+                                 const long* rows, long n_rows, int which, double lam, double* out)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < n_rows; ++r) {
+        long i = rows[r];
+        long lo = cu[doc[i]], hi = cu[doc[i] + 1];
+        double* o = out + r * d;
+        for (long a = 0; a < d; ++a) o[a] = 0.0;
+        if (which <= 1) {
+            for (long j = lo; j <= i; ++j) {
+                double w = pow(lam, (double)(i - j));
+                double s = w * (which == 0 ? dot(Q + i * d, K + j * d, d) : dot(dO + i * d, V + j * d, d));
+                const double* x = (which == 0 ? V : K) + j * d;
+                for (long a = 0; a < d; ++a) o[a] += s * x[a];
+            }
+        } else {
+            for (long q = i; q < hi; ++q) {
+                double w = pow(lam, (double)(q - i));
+                double s = w * (which == 2 ? dot(dO + q * d, V + i * d, d) : dot(Q + q * d, K + i * d, d));
+                const double* x = (which == 2 ? Q : dO) + q * d;
+                for (long a = 0; a < d; ++a) o[a] += s * x[a];
+            }
+        }
+    }
+    free(doc);
+}

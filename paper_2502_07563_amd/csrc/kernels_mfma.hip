@@ -154,14 +154,31 @@ __device__ __forceinline__ void update_tiles(f32x16 (&acc)[TPW], const char* tx,
     }
 }
 
+// The eight bf16 of a 16-byte piece times w, rounded to nearest even.
+__device__ __forceinline__ u32x4 scale_bf16x8(u32x4 x, float w)
+{
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = __builtin_bit_cast(float, x[e] << 16);
+        const float hi = __builtin_bit_cast(float, x[e] & 0xffff0000u);
+        r[e] = pack2(lo * w, hi * w);
+    }
+    return r;
+}
+
 // =====================================================================================
 // Chunk states: M[slot] = X^T Y over the slot's tokens (X = K, Y = V; or Q, dO).
+// With decay (DECAY) the rows of X carry the token's weight lam^(slot end - token), or
+// lam^(token - slot start) when anchor_start is set; the weighted row is rounded to bf16
+// before the product, like every other operand of the matrix cores.
 // =====================================================================================
 constexpr int ST_NW = 8, ST_NT = ST_NW * 64, ST_TPW = 16 / ST_NW;
 
+template <bool DECAY>
 __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* __restrict__ X,
                                                             const char* __restrict__ Y,
-                                                            float* __restrict__ M)
+                                                            float* __restrict__ M, int anchor_start)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* sX = smem;                     // 2 stages
@@ -179,11 +196,20 @@ __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* 
         for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
 
     const int nblk = (len + KB - 1) / KB;
+    const float l2 = DECAY ? decay_log2(g, grp) : 0.f;
     BlockRegs<ST_NT> regs;
     load_block<ST_NT>(regs, X, Y, row0, 0, len, tid);
     for (int blk = 0; blk < nblk; ++blk) {
         char* tx = sX + (blk & 1) * STAGE_BYTES;
         char* ty = sY + (blk & 1) * STAGE_BYTES;
+        if (DECAY) {
+#pragma unroll
+            for (int u = 0; u < BlockRegs<ST_NT>::LPT; ++u) {
+                const int tok = blk * KB + ((tid + u * ST_NT) >> 4);
+                const float wt = exp2f((float)(anchor_start ? tok : len - 1 - tok) * l2);
+                regs.x[u] = scale_bf16x8(regs.x[u], wt);
+            }
+        }
         store_block<ST_NT>(regs, tx, ty, tid);
         if (blk + 1 < nblk) load_block<ST_NT>(regs, X, Y, row0, (blk + 1) * KB, len, tid);
         __syncthreads();
@@ -739,6 +765,263 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
 }
 
 // =====================================================================================
+// Fused attention pass with scalar decay: out_i = sum_j lam^|i-j| (a_i . bk_j) cv_j over the
+// allowed pairs plus the decayed inter-chunk term.  Same tiles, stages and layouts as
+// attn_mfma_kernel<128> (four waves), with these differences:
+//   - Anti-causal problems walk the slot BACKWARDS (blocks and chunks in descending order, the
+//     slot state being the exclusive suffix): with decay the forward walk with a subtracted
+//     suffix would have to divide by lam at every step.  Both directions therefore take the
+//     state snapshot and the inter-chunk product at the start of a chunk.
+//   - Each wave multiplies the rows of the Bk tile it staged by the token's weight as seen from
+//     the block's last token (causal, lam^(63-b)) or first token (anti-causal, lam^b) before the
+//     block barrier.  The state update then is lam^64 * state + Bk~^T Cv, and a score computed
+//     from the weighted rows needs only a factor per query, lam^(i - block start - 63) resp.
+//     lam^(block start - i), to become lam^|i-j| (a_i . bk_j); the exponents stay within +-63.
+//   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the chunk)
+//     or lam^(chunk length - a) (anti-causal).
+// The rows of A are fetched with ordinary loads here; this kernel is not tuned like the
+// undecayed one.
+// =====================================================================================
+__global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
+                                                              AttnProblem p2, int nprob)
+{
+    constexpr int C = 128, NW = 4, TPW = 4, BPC = C / KB, IPW = 16 / NW, DPS = 2 * IPW, NOP = 8;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sK = smem;                              // Bk stages
+    char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
+    char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
+    char* sO = sM + D * ROWB;                     // output staging, 4 KiB per wave
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, l32 = lane & 31;
+    const unsigned unit = (blockIdx.x / (8u * nprob)) * 8u + (blockIdx.x & 7u);
+    const int prob = (int)(blockIdx.x >> 3) % nprob;
+    if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
+    const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
+    const AttnProblem& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
+    const char* __restrict__ A = pr.A;
+    const char* __restrict__ Bk = pr.Bk;
+    const char* __restrict__ Cv = pr.Cv;
+    char* __restrict__ out = pr.out;
+    const bool rev = pr.anti != 0;
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    if (len <= 0) return;
+    const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
+    const float l2 = decay_log2(g, grp);
+    const int rb = w, t0 = w * TPW;
+
+    const int nch = (len + C - 1) / C;
+    const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
+    uint32_t dvo[IPW];
+#pragma unroll
+    for (int u = 0; u < IPW; ++u) dvo[u] = dma_lane_off(w * IPW + u, lane);
+    // walk position i -> block of the slot
+    auto issue = [&](int i) {
+        const int bb = rev ? NB - 1 - i : i;
+        dma_block<NW>(Bk, Cv, row0, bb * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane, dvo);
+    };
+    issue(0);
+    if (NB > 1) issue(1);
+
+    // running state tiles, C/D layout: rows = d_k (first index), columns = d_v
+    f32x16 Macc[TPW];
+    {
+        const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+            const int t = t0 + u, a = t >> 2, b = t & 3;
+            if (!pr.transpose_state) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    Macc[u][v] = st[(32 * a + 8 * (v >> 2) + 4 * h + (v & 3)) * D + 32 * b + l32];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 x = *reinterpret_cast<const f32x4*>(st + (32 * b + l32) * D + 32 * a + 8 * q + 4 * h);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Macc[u][4 * q + e] = x[e];
+                }
+            }
+        }
+    }
+
+    LaneOffs<TPW> lo;
+    make_lane_offs<TPW>(lo, lane, t0);
+
+    // weights of the Bk rows this wave stages (row b of the block), and lam^64 for the state
+    float wrow[IPW];
+#pragma unroll
+    for (int u = 0; u < IPW; ++u) {
+        const int b = 4 * (w * IPW + u) + (lane >> 4);
+        wrow[u] = exp2f((float)(rev ? b : KB - 1 - b) * l2);
+    }
+    const float wblk = exp2f((float)KB * l2);
+
+    bf16x8 qf[8];   // this wave's 32 rows of A as B-operand fragments (column = row of A, k = d)
+    auto load_q = [&](int cc) {
+        const int r = cc * C + 32 * rb + l32;
+        const bool ok = r < len;
+        const char* p = A + row0 + (size_t)r * ROWB + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            u32x4 x = ok ? *reinterpret_cast<const u32x4*>(p + 32 * ks) : z;
+            qf[ks] = __builtin_bit_cast(bf16x8, x);
+        }
+    };
+    load_q(rev ? nch - 1 : 0);
+
+    int bi = 0;          // walk position of the block being consumed
+    int prev_nblk = BPC;
+    for (int c = 0; c < nch; ++c) {
+        const int cc = rev ? nch - 1 - c : c;               // chunk of the slot
+        const int b_lo = cc * BPC, b_hi = min(NB, b_lo + BPC);
+        const int nblk = b_hi - b_lo;
+        const int clen = min(C, len - cc * C);
+        const bool last_chunk = (c + 1 == nch);
+
+        // The previous chunk read the snapshot in its first block; one of its later block
+        // barriers separates that from this write unless it had a single block.
+        if (prev_nblk < 2) __syncthreads();
+        write_snapshot<TPW>(sM, Macc, t0, l32, h, false);
+
+        f32x16 Oacc[4];
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+
+        for (int jb = 0; jb < nblk; ++jb, ++bi) {
+            const int bb = rev ? b_hi - 1 - jb : b_lo + jb;   // block of the slot
+            const int jbb = bb - b_lo;                         // its index inside the chunk
+            char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
+            char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+            if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            if (bb * KB + KB > len) zero_tail_rows<NW>(bb * KB, len, tK, tV, w, lane);
+            // weight this wave's own rows of the Bk tile (a whole row takes one weight, so the
+            // swizzle does not matter here)
+#pragma unroll
+            for (int u = 0; u < IPW; ++u) {
+                u32x4* pk = reinterpret_cast<u32x4*>(tK + (4 * (w * IPW + u) + (lane >> 4)) * ROWB + (lane & 15) * 16);
+                *pk = scale_bf16x8(*pk, wrow[u]);
+            }
+            __syncthreads();   // block complete and weighted in LDS; every wave is past the previous one
+            if (bi + 2 < NB) issue(bi + 2);
+
+            if (jb == 0) {
+                inter_product<NOP>(Oacc, sM, qf, lo.nat);
+                // the state sits one token before the chunk (causal) or one after it (anti-causal)
+                const float wq = exp2f((float)(rev ? clen - (32 * rb + l32) : 32 * rb + l32 + 1) * l2);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) Oacc[tv][v] *= wq;
+            }
+
+            bf16x8 bufA[NOP], bufB[NOP];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int kt = 2 * jbb + half;      // 32-key tile index inside the chunk
+                const bool active = rev ? (kt >= rb) : (kt <= rb);
+                if (!active) continue;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks]);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks + 4]);
+                SCHED_FENCE();
+                f32x16 sc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+                    bufA[tv] = lds_read_tr8_at(tV + half * (32 * ROWB), lo.pv[tv][0], lo.pv[tv][1]);
+                SCHED_FENCE();
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+                    bufB[tv] = lds_read_tr8_at(tV + half * (32 * ROWB) + 16 * ROWB, lo.pv[tv][0], lo.pv[tv][1]);
+                SCHED_FENCE();
+                {
+                    // from the row weights of the block to lam^|i-j|: one factor per query
+                    const int qi = 32 * rb + l32 - KB * jbb;   // query index relative to the block's start
+                    const float f = exp2f((float)(rev ? -qi : qi - (KB - 1)) * l2);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+                        const bool keep = (kt != rb) || (rev ? (key >= l32) : (key <= l32));
+                        sc[v] = keep ? sc[v] * f : 0.f;
+                    }
+                }
+                {
+                    u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
+                    bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                    for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
+                }
+                {
+                    u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                    bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                    for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+                }
+                SCHED_FENCE();
+            }
+
+            if (!last_chunk) {
+                // running state = lam^n * state + (weighted Bk block)^T Cv block, n = the block's
+                // tokens (fewer than 64 only in the slot's last block, which the backward walk
+                // meets first)
+                const float wb = (bb * KB + KB <= len) ? wblk : exp2f((float)(len - bb * KB) * l2);
+#pragma unroll
+                for (int u = 0; u < TPW; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) Macc[u][v] *= wb;
+#pragma unroll
+                for (int ks = 0; ks < KB / 16; ++ks) {
+                    rd_update<TPW, NOP>(bufA, tK, tV, ks, lo);
+                    SCHED_FENCE();
+                    mm_update<TPW, NOP>(Macc, bufA);
+                    SCHED_FENCE();
+                }
+            }
+        }
+        prev_nblk = nblk;
+        if (!last_chunk) load_q(rev ? cc - 1 : cc + 1);
+
+        {
+            char* stg = sO + w * 4096;
+            const int rbase = cc * C + 32 * rb;
+#pragma unroll
+            for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+                for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16& o = Oacc[2 * hv + tvv];
+                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                        *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                    if (rbase + row < len)
+                        *reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                }
+            }
+        }
+    }
+}
+
+// =====================================================================================
 // Rows times a slot state, for the path without masking: out = A W over the rows of one slot,
 // W = state[slot] or its transpose (O_t = Q_t M_{1:T}; dQ_t = dO_t M_{1:T}^T, dK_t = V_t
 // dM_{1:T}^T, dV_t = K_t dM_{1:T}).  The work is two passes over HBM per product (rows in,
@@ -882,26 +1165,46 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
 bool mfma_path_supported(const Geom& g, int dtype)
 {
     // The kernels tile a slot in their own chunks (the result does not depend on the chunk
-    // length), so every C of the caller is served.  They implement the undecayed mask only.
-    return dtype == LASP2_BF16 && g.d == D && g.decay == nullptr;
+    // length), so every C of the caller is served.  With decay the factors must keep lam^-63
+    // and lam^63 well inside the fp32 / bf16 range (decided on the host, see make_geom).
+    return dtype == LASP2_BF16 && g.d == D && (g.decay == nullptr || g.decay_mfma);
 }
 
-hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M, hipStream_t st)
+hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M, int anchor_start,
+                              hipStream_t st)
 {
     constexpr int smem = 4 * STAGE_BYTES;   // 64 KiB
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(states_mfma_kernel),
+    auto kern = g.decay ? states_mfma_kernel<true> : states_mfma_kernel<false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     dim3 grid(g.T_s, g.G), block(ST_NT);
-    hipLaunchKernelGGL(states_mfma_kernel, grid, block, smem, st, g, static_cast<const char*>(K),
-                       static_cast<const char*>(V), M);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, static_cast<const char*>(K),
+                       static_cast<const char*>(V), M, anchor_start);
     return hipGetLastError();
 }
+
+namespace {
+hipError_t launch_attn_decay(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
+                             const AttnProblem& p2, int nprob, hipStream_t st)
+{
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 4 * 4096;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decay_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
+    const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
+    dim3 grid(gx), block(256);
+    hipLaunchKernelGGL(attn_decay_mfma_kernel, grid, block, smem, st, g, p0, p1, p2, nprob);
+    return hipGetLastError();
+}
+}  // namespace
 
 hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
                                 const float* P, void* O, hipStream_t st)
 {
     const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
+    if (g.decay) return launch_attn_decay(g, p, p, p, 1, st);
     if (wide_chunks(g)) return launch_attn_C<256>(g, p, p, p, 1, st);
     return launch_attn_C<128>(g, p, p, p, 1, st);
 }
@@ -917,6 +1220,7 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pq = make_problem(dO, V, K, P, dQ, 1, 0);
     const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
+    if (g.decay) return launch_attn_decay(g, pq, pv, pk, 3, st);
     if (wide_chunks(g)) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }

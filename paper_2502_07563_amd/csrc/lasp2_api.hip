@@ -64,6 +64,14 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     g->G = (int32_t)G;
     g->H = desc->H > 0 ? desc->H : 1;
     g->decay = desc->decay_dev;
+    // The MFMA decay kernels weight rows by lam^(0..63) in bf16 and undo it with lam^-(0..63)
+    // in fp32; 0.35^63 = 2e-29 keeps both far from the ends of the exponent range.
+    g->decay_mfma = 0;
+    if (desc->decay_host) {
+        g->decay_mfma = 1;
+        for (int h = 0; h < desc->H; ++h)
+            if (desc->decay_host[h] < 0.35f) g->decay_mfma = 0;
+    }
     g->N = desc->N;
     g->d = desc->d;
     g->C = desc->C;
@@ -90,7 +98,7 @@ int from_hip(hipError_t e) { return e == hipSuccess ? LASP2_OK : LASP2_ERR_LAUNC
 hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, float* M,
                       int anchor_start, hipStream_t st)
 {
-    if (mfma_path_supported(g, dtype)) return launch_states_mfma(g, K, V, M, st);
+    if (mfma_path_supported(g, dtype)) return launch_states_mfma(g, K, V, M, anchor_start, st);
     return launch_states_generic(g, dtype, K, V, M, anchor_start, st);
 }
 
@@ -186,7 +194,7 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     // forwards and subtract, see attn_mfma_kernel).
     hipError_t e = run_states(g, desc->dtype, Q, dO, dR, 1, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    e = launch_state_prefix(g, dR, dR, 1, fast ? 1 : 0, st);
+    e = launch_state_prefix(g, dR, dR, 1, (fast && !g.decay) ? 1 : 0, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     if (fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is

@@ -21,6 +21,7 @@ struct Geom {
     const int32_t* cu;    // packed: DEVICE pointer to n_seqs+1 offsets
     int32_t H;            // heads (group g uses decay[g % H])
     const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
+    int32_t decay_mfma;   // host decision: every factor is large enough for the MFMA decay kernels
 };
 
 // log2 of the decay factor of group grp (0 when there is no decay): lam^e = exp2f(e * log2 lam).
@@ -85,12 +86,13 @@ hipError_t launch_rows_state_generic(const Geom& g, int dtype, const void* A, co
 // bf16 MFMA kernels (d = 128; they tile slots in their own chunks, so any C).
 bool mfma_path_supported(const Geom& g, int dtype);
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M,
-                              hipStream_t st);
+                              int anchor_start, hipStream_t st);
 // O = fused intra + inter pass with prefix states P.
 hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
                                 const float* P, void* O, hipStream_t st);
 // dQ, dV, dK in one launch.  P: exclusive prefix states of K^T V (from the forward);
-// dR: INCLUSIVE suffix states of Q^T dO (slot s holds the sum over slots >= s of its document).
+// dR: INCLUSIVE suffix states of Q^T dO (slot s holds the sum over slots >= s of its document);
+// with decay: the EXCLUSIVE decayed suffix of the start-anchored states.
 hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
                                 const void* dO, const float* P, const float* dR, void* dQ, void* dK,
                                 void* dV, hipStream_t st);

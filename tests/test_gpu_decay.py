@@ -56,7 +56,10 @@ def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None, lam=None):
     for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs):
         errs[name] = rel_l2(to_host(got), ref)
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
-    assert max(errs["M"], errs["P"], errs["dP"]) <= TOL_STATE, errs
+    # The MFMA kernels (bf16, d = 128, every factor >= 0.35) round the weighted rows lam^e k to
+    # bf16 before the product, so their states carry bf16 rounding; the plain kernels weight in fp32.
+    mfma = dtype == "bf16" and d == 128 and float(lam.min()) >= 0.35
+    assert max(errs["M"], errs["P"], errs["dP"]) <= (TOL["bf16"] if mfma else TOL_STATE), errs
     for k in ("O", "dQ", "dK", "dV"):
         assert errs[k] <= TOL[dtype], errs
     return dict(O=O, dQ=dQ, dK=dK, dV=dV, P=P)
@@ -68,9 +71,16 @@ def test_fp32_shapes(oracle, N, d, C, L):
     _run(oracle, 2, 3, N, d, C, L, "f32", seed=90 + N)
 
 
-@pytest.mark.parametrize("N,d,C,L", [(1024, 128, 256, 512), (900, 64, 128, 256), (300, 128, 64, 0)])
+@pytest.mark.parametrize("N,d,C,L", [(1024, 128, 256, 512), (900, 64, 128, 256), (300, 128, 64, 0),
+                                     (2304, 128, 256, 1024), (1900, 128, 256, 512), (200, 128, 256, 0),
+                                     (777, 128, 50, 150), (67, 128, 1, 3)])
 def test_bf16_shapes(oracle, N, d, C, L):
     _run(oracle, 1, 3, N, d, C, L, "bf16", seed=110 + N)
+
+
+def test_bf16_d128_strong_decay_takes_the_plain_kernels(oracle):
+    """A factor below 0.35 is outside the range the MFMA decay kernels are built for."""
+    _run(oracle, 1, 3, 700, 128, 128, 256, "bf16", seed=115, lam=[0.2, 0.99, 0.05])
 
 
 @pytest.mark.parametrize("dtype,d,C,L", [("f32", 32, 64, 128), ("bf16", 128, 128, 256)])

@@ -146,3 +146,33 @@ def test_cfg3_without_masking(oracle):
         errs["dS"] = rel_l2(_gpu_group(dS, g), dS_ref[0])
         assert max(errs["S"], errs["dS"]) <= TOL_STATE, (g, errs)
         print(f"group {g}:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+
+
+def test_cfg3_with_decay(oracle):
+    """Scalar decay at the size bench.py times, Retention's per-head schedule 1 - 2^(-5-h):
+    sampled rows of O, dQ, dK, dV of two heads against the decayed definition."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    cfg = synth.CONFIGS["cfg3"]
+    B, H, N, d, C, L, dtype, seed = (cfg[k] for k in ("B", "H", "N", "d", "C", "L", "dtype", "seed"))
+    lam = (1.0 - 2.0 ** (-5.0 - np.arange(H))).astype(np.float32)
+    p = bd.Problem(B, H, N, d, C, L, dtype, decay=lam)
+    dev = {}
+    for n in ("Q", "K", "V", "dO"):
+        host = synth.gen_tensor(seed, n, B * H, N, d, dtype, workers=16)
+        dev[n] = torch.from_numpy(host).reshape(B, H, N, d).to("cuda").to(p.torch_dtype)
+        del host
+    O, P = bd.forward(p, dev["Q"], dev["K"], dev["V"])
+    dQ, dK, dV, _ = bd.backward(p, dev["Q"], dev["K"], dev["V"], dev["dO"], P)
+    torch.cuda.synchronize()
+    out = dict(O=O, dQ=dQ, dK=dK, dV=dV)
+    rng = np.random.default_rng(34)
+    for g in (0, 9):
+        x = _host_group(cfg, g)
+        rows = np.unique(np.concatenate([rng.integers(0, N, 24), [0, N - 1, L - 1, L, 127, 128]])).astype(np.int64)
+        errs = {}
+        for which, k in enumerate(("O", "dQ", "dK", "dV")):
+            ref = oracle.def_rows_decay(x["Q"], x["K"], x["V"], x["dO"], rows, which, float(lam[g]))
+            errs[k] = rel_l2(_gpu_group(out[k], g)[rows], ref)
+            assert errs[k] <= TOL[dtype], (g, errs)
+        print(f"group {g}:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)

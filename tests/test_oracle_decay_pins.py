@@ -148,3 +148,19 @@ def test_gradient_by_finite_differences(oracle):
             am = {"Q": (Xm, K, V), "K": (Q, Xm, V), "V": (Q, K, Xm)}[name]
             fd = (loss(*ap) - loss(*am)) / (2 * eps)
             assert abs(fd - dX[0, i, a]) <= 1e-6 * max(1.0, abs(fd)), (name, i, a)
+
+
+def test_row_sampler_matches_full_definition(oracle):
+    cu = [0, 7, 8, 40, 61]
+    Q, K, V, dO = _rand(1, 61, 8, 38)
+    lam = 0.8
+    full = (oracle.fwd_def_decay(Q, K, V, lam, cu),) + oracle.bwd_def_decay(Q, K, V, dO, lam, cu)
+    rows = np.array([60, 0, 7, 8, 39, 40, 6])
+    for which in range(4):
+        got = oracle.def_rows_decay(Q[0], K[0], V[0], dO[0], rows, which, lam, cu)
+        assert _rel(got, full[which][0][rows]) < 1e-13
+    g = json.load(open(os.path.join(GOLD, "decay_hand_example.json")))
+    A = {k: np.array(g[k], dtype=np.float64) for k in ("Q", "K", "V", "dO", "O", "dQ", "dK", "dV")}
+    for which, key in enumerate(("O", "dQ", "dK", "dV")):
+        got = oracle.def_rows_decay(A["Q"], A["K"], A["V"], A["dO"], np.array([2, 0, 1]), which, g["lam"])
+        assert np.array_equal(got, A[key][[2, 0, 1]])
