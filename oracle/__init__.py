@@ -428,3 +428,45 @@ def def_rows_decay(Q, K, V, dO, rows, which, lam, cu=None):
                                        ctypes.c_int(which), ctypes.c_double(float(lam)),
                                        out.ctypes.data_as(_c_dp))
     return out
+
+
+# ---------------------------------------------------------------------------
+# Softmax attention (Algorithm "AllGather-based Context Parallelism", compute line)
+# ---------------------------------------------------------------------------
+
+def softmax_fwd(Q, K, V, causal=False, cu=None):
+    """O = Softmax(Q K^T / sqrt(d)) V per group and document; returns (O, lse)."""
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    O = np.empty((G, N, d)); lse = np.empty((G, N))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_softmax_fwd(q, k, v, O.ctypes.data_as(_c_dp), lse.ctypes.data_as(_c_dp),
+                                    ctypes.c_long(G), ctypes.c_long(N), ctypes.c_long(d), c,
+                                    ctypes.c_long(len(cu) - 1), ctypes.c_int(1 if causal else 0))
+    return O, lse
+
+
+def softmax_bwd(Q, K, V, dO, causal=False, cu=None):
+    G, N, d = _gnd(Q)
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO)
+    dQ = np.empty((G, N, d)); dK = np.empty((G, N, d)); dV = np.empty((G, N, d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_softmax_bwd(q, k, v, g, dQ.ctypes.data_as(_c_dp), dK.ctypes.data_as(_c_dp),
+                                    dV.ctypes.data_as(_c_dp), ctypes.c_long(G), ctypes.c_long(N),
+                                    ctypes.c_long(d), c, ctypes.c_long(len(cu) - 1),
+                                    ctypes.c_int(1 if causal else 0))
+    return dQ, dK, dV
+
+
+def softmax_rows(Q, K, V, rows, causal=False, cu=None):
+    """Rows `rows` of the softmax output and their log-sum-exp for ONE group; Q,K,V are [N, d]."""
+    N, d = Q.shape
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V)
+    rows, r = _l(rows)
+    out = np.empty((len(rows), d)); lse = np.empty(len(rows))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_softmax_rows(q, k, v, ctypes.c_long(N), ctypes.c_long(d), c,
+                                     ctypes.c_long(len(cu) - 1), r, ctypes.c_long(len(rows)),
+                                     ctypes.c_int(1 if causal else 0), out.ctypes.data_as(_c_dp),
+                                     lse.ctypes.data_as(_c_dp))
+    return out, lse

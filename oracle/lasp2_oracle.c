@@ -33,6 +33,9 @@
  *               Lightning Attention layers of the paper's Table 2 use; the paper prints no
  *               formulas for them, so the definition below is the reference and the
  *               recurrence and chunked steps are derived from it.
+ *   softmax_*    : standard softmax attention, O = Softmax(Q K^T / sqrt(d)) V, the local
+ *               computation of Algorithm "AllGather-based Context Parallelism" (the
+ *               standard-attention layers of the hybrid model), with its gradient.
  *   nomask_*_def / state_total / rows_times_state :
  *               linear attention without the mask (every token of a document
  *               attends to every token of it): the double-sum definition and
@@ -910,6 +913,122 @@ void lasp2_oracle_def_rows_decay(const double* Q, const double* K, const double*
                 for (long a = 0; a < d; ++a) o[a] += s * x[a];
             }
         }
+    }
+    free(doc);
+}
+
+/* ================================================================== */
+/* Softmax attention, the compute line of Algorithm "AllGather-based   */
+/* Context Parallelism": O = Softmax(Q K^T / sqrt(d)) V, row-wise, over */
+/* the keys of the query's document; causal != 0 keeps keys j <= i only */
+/* (the algorithm prints no mask; the text names causal and document    */
+/* masks as what the gathered form makes easy).                         */
+/* lse (may be NULL) receives log(sum_j exp(s_ij)) per row.             */
+/* ================================================================== */
+void lasp2_oracle_softmax_fwd(const double* Q, const double* K, const double* V,
+                              double* O, double* lse, long G, long N, long d,
+                              const long* cu, long n_docs, int causal)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+    double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (long g = 0; g < G; ++g) {
+        for (long i = 0; i < N; ++i) {
+            long lo = cu[doc[i]], hi = causal ? i + 1 : cu[doc[i] + 1];
+            double* sc = (double*)malloc(sizeof(double) * (size_t)(hi - lo));
+            double mx = -INFINITY;
+            for (long j = lo; j < hi; ++j) {
+                sc[j - lo] = scale * dot(Q + (g * N + i) * d, K + (g * N + j) * d, d);
+                if (sc[j - lo] > mx) mx = sc[j - lo];
+            }
+            double sum = 0.0;
+            for (long j = lo; j < hi; ++j) { sc[j - lo] = exp(sc[j - lo] - mx); sum += sc[j - lo]; }
+            double* o = O + (g * N + i) * d;
+            for (long b = 0; b < d; ++b) o[b] = 0.0;
+            for (long j = lo; j < hi; ++j) {
+                double p = sc[j - lo] / sum;
+                const double* v = V + (g * N + j) * d;
+                for (long b = 0; b < d; ++b) o[b] += p * v[b];
+            }
+            if (lse) lse[g * N + i] = mx + log(sum);
+            free(sc);
+        }
+    }
+    free(doc);
+}
+
+/*
+ * Gradient of <dO, O> for softmax attention.  With P the row-softmax of the scaled scores,
+ * dP_ij = dO_i . v_j and delta_i = sum_j P_ij dP_ij (= dO_i . O_i):
+ *   dS_ij = P_ij (dP_ij - delta_i),
+ *   dQ_i = scale sum_j dS_ij k_j,  dK_j = scale sum_i dS_ij q_i,  dV_j = sum_i P_ij dO_i.
+ */
+void lasp2_oracle_softmax_bwd(const double* Q, const double* K, const double* V,
+                              const double* dO, double* dQ, double* dK, double* dV,
+                              long G, long N, long d, const long* cu, long n_docs, int causal)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+    double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long g = 0; g < G; ++g) {
+        memset(dQ + g * N * d, 0, sizeof(double) * (size_t)(N * d));
+        memset(dK + g * N * d, 0, sizeof(double) * (size_t)(N * d));
+        memset(dV + g * N * d, 0, sizeof(double) * (size_t)(N * d));
+        for (long i = 0; i < N; ++i) {
+            long lo = cu[doc[i]], hi = causal ? i + 1 : cu[doc[i] + 1];
+            long n = hi - lo;
+            double* p = (double*)malloc(sizeof(double) * (size_t)n);
+            double* dp = (double*)malloc(sizeof(double) * (size_t)n);
+            double mx = -INFINITY, sum = 0.0, delta = 0.0;
+            for (long j = lo; j < hi; ++j) {
+                p[j - lo] = scale * dot(Q + (g * N + i) * d, K + (g * N + j) * d, d);
+                if (p[j - lo] > mx) mx = p[j - lo];
+            }
+            for (long j = lo; j < hi; ++j) { p[j - lo] = exp(p[j - lo] - mx); sum += p[j - lo]; }
+            for (long j = lo; j < hi; ++j) {
+                p[j - lo] /= sum;
+                dp[j - lo] = dot(dO + (g * N + i) * d, V + (g * N + j) * d, d);
+                delta += p[j - lo] * dp[j - lo];
+            }
+            for (long j = lo; j < hi; ++j) {
+                double ds = p[j - lo] * (dp[j - lo] - delta);
+                for (long a = 0; a < d; ++a) {
+                    dQ[(g * N + i) * d + a] += scale * ds * K[(g * N + j) * d + a];
+                    dK[(g * N + j) * d + a] += scale * ds * Q[(g * N + i) * d + a];
+                    dV[(g * N + j) * d + a] += p[j - lo] * dO[(g * N + i) * d + a];
+                }
+            }
+            free(p);
+            free(dp);
+        }
+    }
+    free(doc);
+}
+
+/* Selected rows of the softmax output (one group; Q,K,V are [N][d]). */
+void lasp2_oracle_softmax_rows(const double* Q, const double* K, const double* V, long N, long d,
+                               const long* cu, long n_docs, const long* rows, long n_rows,
+                               int causal, double* out, double* lse)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+    double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < n_rows; ++r) {
+        long i = rows[r];
+        long lo = cu[doc[i]], hi = causal ? i + 1 : cu[doc[i] + 1];
+        double* sc = (double*)malloc(sizeof(double) * (size_t)(hi - lo));
+        double mx = -INFINITY, sum = 0.0;
+        for (long j = lo; j < hi; ++j) {
+            sc[j - lo] = scale * dot(Q + i * d, K + j * d, d);
+            if (sc[j - lo] > mx) mx = sc[j - lo];
+        }
+        for (long j = lo; j < hi; ++j) { sc[j - lo] = exp(sc[j - lo] - mx); sum += sc[j - lo]; }
+        double* o = out + r * d;
+        for (long b = 0; b < d; ++b) o[b] = 0.0;
+        for (long j = lo; j < hi; ++j)
+            for (long b = 0; b < d; ++b) o[b] += sc[j - lo] / sum * V[j * d + b];
+        if (lse) lse[r] = mx + log(sum);
+        free(sc);
     }
     free(doc);
 }
