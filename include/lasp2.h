@@ -209,6 +209,24 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                      void* dQ, void* dK, void* dV,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * ---- Standard (softmax) attention of the hybrid model (LASP-2H; Sec. "Hybrid
+ * Model Sequence Parallelism", Algorithm "AllGather-based Context
+ * Parallelism") ----
+ * Line "O_t = Softmax(Q_t K^T / sqrt(d)) V" with K and V gathered, i.e. whole
+ * in HBM here; every query block is what one rank computes.  Row-wise softmax
+ * over the keys of the query's sequence (packed input: of its document, the
+ * document-level mask the paper names as a reason for the gathered form);
+ * causal != 0 additionally keeps keys j <= i only (the algorithm prints no
+ * mask; Llama-style layers are causal).  C, L and the slots play no part.
+ * In: Q,K,V [B,H,N,d].  Out: O [B,H,N,d] in `dtype`; LSE [B,H,N] fp32, the
+ * natural-log sum of exp of each row's scaled scores (what a backward pass
+ * needs to rebuild the probabilities).  Decay is rejected.  bf16 with d = 128
+ * runs on the matrix cores, everything else on a plain fp32 kernel.
+ */
+int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
+                      const void* V, void* O, float* LSE, int causal, void* stream);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lasp2_status_string(int status);
 

@@ -321,6 +321,116 @@ hipError_t rows_state_generic_T(const Geom& g, const T* A, const float* state, T
     }
 }
 
+// Softmax attention forward for kSmRows queries per workgroup, plain fp32: the keys of the
+// workgroup's range are taken 64 at a time; scores go to LDS, one thread per query keeps the
+// running maximum and sum and turns the scores into exp(s - m), and every thread owns the
+// output elements (query r, columns c, c + 256/kSmRows ...) which it rescales and extends.
+constexpr int kSmRows = 16, kSmKeys = 64;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void softmax_fwd_generic_kernel(Geom g, const T* __restrict__ Q,
+                                                                       const T* __restrict__ K,
+                                                                       const T* __restrict__ V,
+                                                                       T* __restrict__ O,
+                                                                       float* __restrict__ LSE, int causal)
+{
+    constexpr int CPT = kSmRows * D / kThreads;     // output columns per thread (same query)
+    constexpr int TPR = kThreads / kSmRows;         // threads per query
+    __shared__ float sQ[kSmRows][D + 1];
+    __shared__ float sS[kSmRows][kSmKeys + 1];
+    __shared__ float sAlpha[kSmRows], sM[kSmRows], sL[kSmRows];
+    __shared__ int sLo[kSmRows], sHi[kSmRows];
+    const int tid = threadIdx.x, grp = blockIdx.y;
+    const int r0 = blockIdx.x * kSmRows;
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+    const float scale = rsqrtf((float)D);
+
+    if (tid < kSmRows) {
+        const int i = r0 + tid;
+        int lo = 0, hi = 0;
+        if (i < g.N) {
+            lo = 0; hi = g.N;
+            for (int k = 0; k < g.n_seqs; ++k)
+                if (g.cu[k] <= i && i < g.cu[k + 1]) { lo = g.cu[k]; hi = g.cu[k + 1]; }
+            if (causal) hi = i + 1;
+        }
+        sLo[tid] = lo; sHi[tid] = hi;
+        sM[tid] = -INFINITY; sL[tid] = 0.f;
+    }
+    for (int idx = tid; idx < kSmRows * D; idx += kThreads) {
+        const int r = idx / D, a = idx % D;
+        sQ[r][a] = (r0 + r < g.N) ? ld(Q + gbase + (size_t)(r0 + r) * D + a) : 0.f;
+    }
+    __syncthreads();
+    int klo = g.N, khi = 0;
+    for (int r = 0; r < kSmRows; ++r) { klo = min(klo, sHi[r] > sLo[r] ? sLo[r] : g.N); khi = max(khi, sHi[r]); }
+
+    const int myr = tid / TPR, c0 = tid % TPR;
+    float acc[CPT];
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) acc[u] = 0.f;
+
+    for (int k0 = klo; k0 < khi; k0 += kSmKeys) {
+        for (int idx = tid; idx < kSmRows * kSmKeys; idx += kThreads) {
+            const int r = idx % kSmRows, j = idx / kSmRows, key = k0 + j;
+            float sres = -INFINITY;
+            if (key >= sLo[r] && key < sHi[r]) {
+                const T* kr = K + gbase + (size_t)key * D;
+                float a = 0.f;
+                for (int e = 0; e < D; ++e) a = fmaf(sQ[r][e], ld(kr + e), a);
+                sres = a * scale;
+            }
+            sS[r][j] = sres;
+        }
+        __syncthreads();
+        if (tid < kSmRows) {
+            float mx = sM[tid];
+            for (int j = 0; j < kSmKeys; ++j) mx = fmaxf(mx, sS[tid][j]);
+            const float mu = (mx == -INFINITY) ? 0.f : mx;
+            const float alpha = expf(sM[tid] - mu);
+            float ps = 0.f;
+            for (int j = 0; j < kSmKeys; ++j) { const float p = expf(sS[tid][j] - mu); sS[tid][j] = p; ps += p; }
+            sL[tid] = sL[tid] * alpha + ps;
+            sM[tid] = mx;
+            sAlpha[tid] = alpha;
+        }
+        __syncthreads();
+        {
+            const float alpha = sAlpha[myr];
+            const int nk = min(kSmKeys, g.N - k0);
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) acc[u] *= alpha;
+            for (int j = 0; j < nk; ++j) {
+                const float p = sS[myr][j];
+                const T* vr = V + gbase + (size_t)(k0 + j) * D;
+#pragma unroll
+                for (int u = 0; u < CPT; ++u) acc[u] = fmaf(p, ld(vr + c0 + u * TPR), acc[u]);
+            }
+        }
+        __syncthreads();
+    }
+    if (r0 + myr < g.N) {
+        const float inv = 1.f / sL[myr];
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) st(O + gbase + (size_t)(r0 + myr) * D + c0 + u * TPR, acc[u] * inv);
+        if (c0 == 0) LSE[(size_t)grp * g.N + r0 + myr] = sM[myr] + logf(sL[myr]);
+    }
+}
+
+template <typename T>
+hipError_t softmax_fwd_generic_T(const Geom& g, const T* Q, const T* K, const T* V, T* O, float* LSE,
+                                 int causal, hipStream_t st)
+{
+    dim3 grid((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
+    switch (g.d) {
+        case 16: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 16>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
+        case 32: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 32>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
+        case 64: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 64>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
+        default: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 128>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
+    }
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, int anchor, hipStream_t st)
 {
@@ -386,6 +496,18 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const void* A, const vo
                           static_cast<const __hip_bfloat16*>(Bk),
                           static_cast<const __hip_bfloat16*>(Cv), state,
                           static_cast<__hip_bfloat16*>(out), transpose_state, reverse, st);
+}
+
+hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
+                                      const void* V, void* O, float* LSE, int causal, hipStream_t st)
+{
+    if (dtype == LASP2_F32)
+        return softmax_fwd_generic_T(g, static_cast<const float*>(Q), static_cast<const float*>(K),
+                                     static_cast<const float*>(V), static_cast<float*>(O), LSE, causal, st);
+    return softmax_fwd_generic_T(g, static_cast<const __hip_bfloat16*>(Q),
+                                 static_cast<const __hip_bfloat16*>(K),
+                                 static_cast<const __hip_bfloat16*>(V), static_cast<__hip_bfloat16*>(O),
+                                 LSE, causal, st);
 }
 
 hipError_t launch_state_total(const Geom& g, const float* M, float* S, hipStream_t st)

@@ -1160,6 +1160,256 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
     }
 }
 
+// =====================================================================================
+// Softmax attention forward, O = Softmax(Q K^T / sqrt(d)) V over the keys of the query's document
+// (optionally causal): the local computation of AllGather-based context parallelism, K and V
+// being whole in HBM.  One workgroup (8 waves x 32 rows) per block of 256 queries; the keys
+// stream through the same ring of 64-token LDS stages as in the fused linear pass, scores^T
+// tiles (keys x queries) come from the same MFMA sequence, and the softmax runs online per
+// query, which in this orientation is per lane: lanes l and l+32 hold the two halves of the
+// keys of one query, so a row maximum is 16 register maxima and one cross-lane exchange, the
+// running sum stays a per-lane partial until the end, and rescaling the output accumulators
+// is a per-lane scalar.  exp2 with the scale folded in; masked scores are -inf.
+// Document and causal bounds are per query [lo, hi); a 32-key tile is skipped, taken whole or
+// masked element-wise depending on how it lies against the bounds of the wave's 32 queries.
+// =====================================================================================
+constexpr int SM_NW = 8, SM_QB = SM_NW * 32;
+
+__device__ __forceinline__ float xor32(float x)
+{
+    return __shfl_xor(x, 32, 64);
+}
+
+__device__ __forceinline__ int wave_min_i(int x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+__device__ __forceinline__ int wave_max_i(int x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = max(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// document [lo, hi) that holds token i (unpacked: the whole sequence)
+__device__ __forceinline__ void doc_range(const Geom& g, int i, int& lo, int& hi)
+{
+    lo = 0;
+    hi = g.N;
+    if (g.n_seqs == 0) return;
+    int a = 0, b = g.n_seqs;          // cu[a] <= i < cu[b]
+    while (b - a > 1) {
+        const int m = (a + b) >> 1;
+        if (g.cu[m] <= i) a = m; else b = m;
+    }
+    lo = g.cu[a];
+    hi = g.cu[a + 1];
+}
+
+__global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, const char* __restrict__ Q,
+                                                                      const char* __restrict__ K,
+                                                                      const char* __restrict__ V,
+                                                                      char* __restrict__ O,
+                                                                      float* __restrict__ LSE, int causal,
+                                                                      float scale_log2e)
+{
+    constexpr int NW = SM_NW, DPS = 2 * (16 / NW);
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sK = smem;
+    char* sV = smem + NSTAGE * STAGE_BYTES;
+    char* sO = smem + 2 * NSTAGE * STAGE_BYTES;   // output staging, 4 KiB per wave
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, l32 = lane & 31;
+    // Units (group, query block) are numbered group-major with the later (for a causal mask:
+    // heavier) query blocks first, and each XCD takes a contiguous range of them, so that the
+    // workgroups resident on an XCD mostly share a group's keys in its L2.
+    const int nqb = (g.N + SM_QB - 1) / SM_QB;
+    const unsigned units = (unsigned)g.G * (unsigned)nqb;
+    const unsigned per_xcd = (units + 7u) / 8u;
+    const unsigned unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || unit >= units) return;
+    const int grp = (int)(unit / (unsigned)nqb);
+    const int qb = nqb - 1 - (int)(unit % (unsigned)nqb);
+    const int r0 = qb * SM_QB;                       // first query of the workgroup
+    const int rlast = min(r0 + SM_QB, g.N) - 1;
+    const size_t base = (size_t)grp * g.N * ROWB;
+
+    // key range of the workgroup (uniform) and bounds of this lane's query
+    int blo, bhi, tmp;
+    doc_range(g, r0, blo, tmp);
+    doc_range(g, rlast, tmp, bhi);
+    if (causal) bhi = rlast + 1;
+    const int qi = r0 + 32 * w + l32;                // this lane's query
+    int lo_i = 0, hi_i = 0;                          // empty range for rows past the end
+    if (qi < g.N) {
+        doc_range(g, qi, lo_i, hi_i);
+        if (causal) hi_i = qi + 1;
+    }
+    // bounds over the wave's valid queries, for the per-tile decision
+    const bool valid = qi < g.N;
+    const int lo_min = wave_min_i(valid ? lo_i : g.N), lo_max = wave_max_i(valid ? lo_i : 0);
+    const int hi_min = wave_min_i(valid ? hi_i : g.N), hi_max = wave_max_i(valid ? hi_i : 0);
+
+    const int kb0 = blo / KB, kb1 = (bhi + KB - 1) / KB;   // key blocks [kb0, kb1)
+    const int NBK = kb1 - kb0;
+    uint32_t dvo[16 / NW];
+#pragma unroll
+    for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
+    auto issue = [&](int i) {
+        dma_block<NW>(K, V, base, (kb0 + i) * KB, g.N, sK + (i % NSTAGE) * STAGE_BYTES,
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane, dvo);
+    };
+    issue(0);
+    if (NBK > 1) issue(1);
+
+    int nat[8], pv[4][2];
+    {
+        const int i = lane & 15, g2 = (lane >> 4) & 1;
+        const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) nat[ks] = tile_off(l32, 2 * ks + h);
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) {
+            pv[tv][0] = tr_off(4 * h + rl, 32 * tv + cl);
+            pv[tv][1] = tr_off(8 + 4 * h + rl, 32 * tv + cl);
+        }
+    }
+
+    // this wave's 32 queries as B-operand fragments (column = query, k = d); zero past the end
+    bf16x8 qf[8];
+    {
+        const char* p = Q + base + (size_t)min(qi, g.N - 1) * ROWB + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            const u32x4 x = *reinterpret_cast<const u32x4*>(p + 32 * ks);
+            qf[ks] = __builtin_bit_cast(bf16x8, valid ? x : z);
+        }
+    }
+
+    f32x16 Oacc[4];
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+    float m = -INFINITY;   // running maximum of scale_log2e * score (shared by lanes l, l+32)
+    float lsum = 0.f;      // this lane's part of the running sum of exp2(. - m)
+
+    for (int bi = 0; bi < NBK; ++bi) {
+        char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
+        char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+        const int k0b = (kb0 + bi) * KB;
+        if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+        if (k0b + KB > g.N) zero_tail_rows<NW>(k0b, g.N, tK, tV, w, lane);
+        __syncthreads();   // block complete in LDS; every wave is past the previous block
+        if (bi + 2 < NBK) issue(bi + 2);
+
+        bf16x8 bufA[4], bufB[4];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int k0 = k0b + 32 * half;          // first key of the tile
+            if (k0 >= hi_max || k0 + 32 <= lo_min) continue;   // no query of this wave sees it
+            const bool whole = (k0 >= lo_max) && (k0 + 32 <= hi_min);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), nat[ks]);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tK + half * (32 * ROWB), nat[ks + 4]);
+            SCHED_FENCE();
+            f32x16 sc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufA[tv] = lds_read_tr8_at(tV + half * (32 * ROWB), pv[tv][0], pv[tv][1]);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufB[tv] = lds_read_tr8_at(tV + half * (32 * ROWB) + 16 * ROWB, pv[tv][0], pv[tv][1]);
+            SCHED_FENCE();
+            if (!whole) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    sc[v] = (key >= lo_i && key < hi_i) ? sc[v] : -INFINITY;
+                }
+            }
+            // online softmax for this lane's query
+            float mx = sc[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v]);
+            mx = fmaxf(mx, xor32(mx));
+            const float m_new = fmaxf(m, mx * scale_log2e);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // nothing seen yet: all terms are 0
+            const float alpha = exp2f(m - m_use);
+            float ps = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sc[v] = exp2f(fmaf(sc[v], scale_log2e, -m_use));
+                ps += sc[v];
+            }
+            lsum = fmaf(lsum, alpha, ps);
+            if (__any(m_new > m)) {
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) Oacc[tv][v] *= alpha;
+            }
+            m = m_new;
+            {
+                u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
+            }
+            {
+                u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+            }
+            SCHED_FENCE();
+        }
+    }
+
+    // normalise, write the log-sum-exp, store through the wave's LDS patch
+    const float ltot = lsum + xor32(lsum);
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    if (valid && h == 0) LSE[(size_t)grp * g.N + qi] = (m + log2f(ltot)) * 0.6931471805599453f;
+    {
+        char* stg = sO + w * 4096;
+        const int rbase = r0 + 32 * w;
+#pragma unroll
+        for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+            for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16& o = Oacc[2 * hv + tvv];
+                    u32x2 pk = {pack2(o[4 * q] * inv, o[4 * q + 1] * inv), pack2(o[4 * q + 2] * inv, o[4 * q + 3] * inv)};
+                    *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                if (rbase + row < g.N)
+                    *reinterpret_cast<u32x4*>(O + base + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 bool mfma_path_supported(const Geom& g, int dtype)
@@ -1240,6 +1490,25 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
     const unsigned gx = (unsigned)n * ((units + 7u) & ~7u);
     dim3 grid(gx), block(RS_NW * 64);
     hipLaunchKernelGGL(rows_state_mfma_kernel, grid, block, smem, st, g, a[0], a[1], a[2], n);
+    return hipGetLastError();
+}
+
+bool softmax_mfma_supported(const Geom& g, int dtype) { return dtype == LASP2_BF16 && g.d == D; }
+
+hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V, void* O,
+                                   float* LSE, int causal, hipStream_t st)
+{
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + SM_NW * 4096;   // 128 KiB
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_fwd_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned nqb = ((unsigned)g.N + SM_QB - 1) / SM_QB;
+    const unsigned units = (unsigned)g.G * nqb;
+    const unsigned gx = 8u * ((units + 7u) / 8u);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.d);
+    hipLaunchKernelGGL(softmax_fwd_mfma_kernel, dim3(gx), dim3(SM_NW * 64), smem, st, g,
+                       static_cast<const char*>(Q), static_cast<const char*>(K),
+                       static_cast<const char*>(V), static_cast<char*>(O), LSE, causal, scale_log2e);
     return hipGetLastError();
 }
 

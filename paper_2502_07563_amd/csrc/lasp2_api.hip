@@ -273,6 +273,23 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, con
     return from_hip(launch_rows_state_generic(g, desc->dtype, K, dS, dV, 0, st));   // dV = K dM
 }
 
+int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                      void* O, float* LSE, int causal, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (g.decay) return LASP2_ERR_DECAY;   // decay belongs to the linear layers
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, K, V, O, LSE});
+    if (rc != LASP2_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (softmax_mfma_supported(g, desc->dtype))
+        return from_hip(launch_softmax_fwd_mfma(g, Q, K, V, O, LSE, causal ? 1 : 0, st));
+    return from_hip(launch_softmax_fwd_generic(g, desc->dtype, Q, K, V, O, LSE, causal ? 1 : 0, st));
+}
+
 const char* lasp2_status_string(int status)
 {
     switch (status) {

@@ -107,4 +107,11 @@ struct RowsStateProblem {
 };
 hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, int n, hipStream_t st);
 
+// Softmax attention forward over the whole sequence (document) of each group.
+hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
+                                      const void* V, void* O, float* LSE, int causal, hipStream_t st);
+bool softmax_mfma_supported(const Geom& g, int dtype);
+hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V, void* O,
+                                   float* LSE, int causal, hipStream_t st);
+
 }  // namespace lasp2

@@ -33,7 +33,7 @@ def test_header_symbols_are_exported():
     names = set(re.findall(r"\b(lasp2_[a-z0-9_]+)\s*\(", text))
     assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
             "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string", "lasp2_state_total",
-            "lasp2_nomask_fwd", "lasp2_nomask_bwd"} <= names
+            "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lasp2.h but not exported"
@@ -119,6 +119,11 @@ def test_null_and_alignment_errors_reach_no_device():
         a = list(args); a[i] = None
         assert lib.lasp2_nomask_bwd(r, *a, ctypes.c_size_t(1 << 40), None) == -1
     assert lib.lasp2_nomask_bwd(r, *args, ctypes.c_size_t(need.value - 1), None) == -5
+    # softmax attention
+    for i in range(5):
+        a = [FAKE] * 5; a[i] = None
+        assert lib.lasp2_softmax_fwd(r, *a, 1, None) == -1
+    assert lib.lasp2_softmax_fwd(r, FAKE, FAKE, ODD, FAKE, FAKE, 0, None) == -6
 
 
 def test_decay_errors():
@@ -136,6 +141,7 @@ def test_decay_errors():
     assert lib.lasp2_state_total(r, FAKE, FAKE, None) == -8
     assert lib.lasp2_nomask_fwd(r, FAKE, FAKE, FAKE, None) == -8
     assert lib.lasp2_nomask_bwd(r, *([FAKE] * 9), ctypes.c_size_t(1 << 40), None) == -8
+    assert lib.lasp2_softmax_fwd(r, *([FAKE] * 5), 1, None) == -8
 
 
 def test_empty_problem_is_ok_without_pointers():
@@ -149,3 +155,4 @@ def test_empty_problem_is_ok_without_pointers():
         assert lib.lasp2_state_total(r, None, None, None) == 0
         assert lib.lasp2_nomask_fwd(r, None, None, None, None) == 0
         assert lib.lasp2_nomask_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0
+        assert lib.lasp2_softmax_fwd(r, *([None] * 5), 0, None) == 0
