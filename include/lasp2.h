@@ -227,6 +227,24 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
 int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                       const void* V, void* O, float* LSE, int causal, void* stream);
 
+/* Bytes of device scratch lasp2_softmax_bwd needs (one fp32 per query row). */
+int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
+
+/*
+ * Backward of lasp2_softmax_fwd (the paper prints the forward of the
+ * standard-attention layers only; this is its gradient).  With P the row
+ * softmax rebuilt from LSE, dP_ij = dO_i . v_j and delta_i = dO_i . O_i:
+ *   dS = P (.) (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d),
+ *   dV = P^T dO.
+ * In: Q,K,V,O,dO [B,H,N,d]; LSE [B,H,N] from the forward; same `causal`.
+ * Out: dQ,dK,dV [B,H,N,d].  `workspace`: device scratch of at least
+ * lasp2_softmax_workspace_size() bytes, 16-byte aligned (receives delta).
+ */
+int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
+                      const void* V, const void* O, const void* dO, const float* LSE,
+                      void* dQ, void* dK, void* dV,
+                      void* workspace, size_t workspace_bytes, int causal, void* stream);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lasp2_status_string(int status);
 

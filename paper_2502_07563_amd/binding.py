@@ -58,11 +58,14 @@ def lib():
         L.lasp2_nomask_fwd.argtypes = [dp, vp, vp, vp, vp]
         L.lasp2_nomask_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.lasp2_softmax_fwd.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_int, vp]
+        L.lasp2_softmax_workspace_size.argtypes = [dp, szp]
+        L.lasp2_softmax_bwd.argtypes = [dp] + [vp] * 10 + [ctypes.c_size_t, ctypes.c_int, vp]
         L.lasp2_status_string.argtypes = [ctypes.c_int]
         L.lasp2_status_string.restype = ctypes.c_char_p
         for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
                      "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_state_total",
-                     "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd"):
+                     "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd",
+                     "lasp2_softmax_workspace_size", "lasp2_softmax_bwd"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -169,6 +172,19 @@ def lasp2_nomask_bwd(p: Problem, Q, K, V, dO, S, dQ, dK, dV, workspace, stream=N
 def lasp2_softmax_fwd(p: Problem, Q, K, V, O, LSE, causal=False, stream=None):
     _check(lib().lasp2_softmax_fwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE),
                                    1 if causal else 0, _stream(stream)), "lasp2_softmax_fwd")
+
+
+def lasp2_softmax_workspace_size(p: Problem) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lasp2_softmax_workspace_size(p.ref, ctypes.byref(out)), "lasp2_softmax_workspace_size")
+    return out.value
+
+
+def lasp2_softmax_bwd(p: Problem, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, causal=False, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lasp2_softmax_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
+                                   1 if causal else 0, _stream(stream)), "lasp2_softmax_bwd")
 
 
 def alloc_states(p: Problem, device="cuda"):

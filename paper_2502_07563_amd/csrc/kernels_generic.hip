@@ -431,6 +431,146 @@ hipError_t softmax_fwd_generic_T(const Geom& g, const T* Q, const T* K, const T*
     return hipGetLastError();
 }
 
+// delta_i = dO_i . O_i for every row (the row sums the softmax backward needs); one wave-sized
+// group of 64 threads per row.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void softmax_delta_kernel(Geom g, const T* __restrict__ O,
+                                                                 const T* __restrict__ dO,
+                                                                 float* __restrict__ delta)
+{
+    const size_t rows = (size_t)g.G * (size_t)g.N;
+    const size_t row = (size_t)blockIdx.x * (kThreads / 64) + threadIdx.x / 64;
+    if (row >= rows) return;
+    const int lane = threadIdx.x % 64;
+    float acc = 0.f;
+    for (int a = lane; a < g.d; a += 64) acc = fmaf(ld(O + row * g.d + a), ld(dO + row * g.d + a), acc);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) delta[row] = acc;
+}
+
+// Softmax attention backward, plain fp32, in two kernels that mirror the forward one.
+// WHICH == 0: dQ for kSmRows queries per workgroup, keys taken 64 at a time:
+//     P = exp(s - lse_i), dP = dO_i . v_j, dS = P (dP - delta_i), dQ_i += scale * dS k_j.
+// WHICH == 1: dK and dV for kSmRows keys per workgroup, queries taken 64 at a time:
+//     dV_j += P dO_i,  dK_j += scale * dS q_i.
+template <typename T, int D, int WHICH>
+__global__ __launch_bounds__(kThreads) void softmax_bwd_generic_kernel(
+    Geom g, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    T* __restrict__ dQ, T* __restrict__ dK, T* __restrict__ dV, int causal)
+{
+    constexpr int CPT = kSmRows * D / kThreads, TPR = kThreads / kSmRows;
+    __shared__ float sA[kSmRows][D + 1];      // the workgroup's own rows: q (dQ) or k (dK, dV)
+    __shared__ float sB[kSmRows][D + 1];      //                            dO (dQ) or v (dK, dV)
+    __shared__ float sP[kSmRows][kSmKeys + 1], sDS[kSmRows][kSmKeys + 1];
+    __shared__ int sLo[kSmRows], sHi[kSmRows];
+    const int tid = threadIdx.x, grp = blockIdx.y;
+    const int r0 = blockIdx.x * kSmRows;
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+    const float scale = rsqrtf((float)D);
+    const T* ownA = WHICH == 0 ? Q : K;
+    const T* ownB = WHICH == 0 ? dO : V;
+
+    // range of partner rows each own row interacts with: keys of a query, or queries of a key
+    if (tid < kSmRows) {
+        const int i = r0 + tid;
+        int lo = 0, hi = 0;
+        if (i < g.N) {
+            lo = 0; hi = g.N;
+            for (int k = 0; k < g.n_seqs; ++k)
+                if (g.cu[k] <= i && i < g.cu[k + 1]) { lo = g.cu[k]; hi = g.cu[k + 1]; }
+            if (causal) { if (WHICH == 0) hi = i + 1; else lo = i; }
+        }
+        sLo[tid] = lo; sHi[tid] = hi;
+    }
+    for (int idx = tid; idx < kSmRows * D; idx += kThreads) {
+        const int r = idx / D, a = idx % D;
+        const bool ok = r0 + r < g.N;
+        sA[r][a] = ok ? ld(ownA + gbase + (size_t)(r0 + r) * D + a) : 0.f;
+        sB[r][a] = ok ? ld(ownB + gbase + (size_t)(r0 + r) * D + a) : 0.f;
+    }
+    __syncthreads();
+    int plo = g.N, phi = 0;
+    for (int r = 0; r < kSmRows; ++r) { plo = min(plo, sHi[r] > sLo[r] ? sLo[r] : g.N); phi = max(phi, sHi[r]); }
+
+    const int myr = tid / TPR, c0 = tid % TPR;
+    float acc1[CPT], acc2[CPT];     // dQ (acc1) or dK (acc1), dV (acc2)
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) { acc1[u] = 0.f; acc2[u] = 0.f; }
+
+    for (int p0 = plo; p0 < phi; p0 += kSmKeys) {
+        for (int idx = tid; idx < kSmRows * kSmKeys; idx += kThreads) {
+            const int r = idx % kSmRows, j = idx / kSmRows, pr = p0 + j;     // own row r, partner row pr
+            float pv = 0.f, ds = 0.f;
+            if (pr >= sLo[r] && pr < sHi[r]) {
+                // query index qi and key index kj of this pair
+                const int qi = WHICH == 0 ? r0 + r : pr;
+                const T* prA = (WHICH == 0 ? K : Q) + gbase + (size_t)pr * D;   // partner k (or q)
+                const T* prB = (WHICH == 0 ? V : dO) + gbase + (size_t)pr * D;  // partner v (or dO)
+                float sdot = 0.f, dpdot = 0.f;
+                for (int e = 0; e < D; ++e) {
+                    sdot = fmaf(sA[r][e], ld(prA + e), sdot);     // q . k
+                    dpdot = fmaf(sB[r][e], ld(prB + e), dpdot);   // dO . v
+                }
+                pv = expf(sdot * scale - LSE[(size_t)grp * g.N + qi]);
+                ds = pv * (dpdot - delta[(size_t)grp * g.N + qi]);
+            }
+            sP[r][j] = pv;
+            sDS[r][j] = ds;
+        }
+        __syncthreads();
+        {
+            const int np = min(kSmKeys, g.N - p0);
+            for (int j = 0; j < np; ++j) {
+                const float ds = sDS[myr][j] * scale, pv = sP[myr][j];
+                const T* xr = (WHICH == 0 ? K : Q) + gbase + (size_t)(p0 + j) * D;
+                const T* yr = dO + gbase + (size_t)(p0 + j) * D;
+#pragma unroll
+                for (int u = 0; u < CPT; ++u) {
+                    acc1[u] = fmaf(ds, ld(xr + c0 + u * TPR), acc1[u]);
+                    if (WHICH == 1) acc2[u] = fmaf(pv, ld(yr + c0 + u * TPR), acc2[u]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (r0 + myr < g.N) {
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const size_t o = gbase + (size_t)(r0 + myr) * D + c0 + u * TPR;
+            if (WHICH == 0) st(dQ + o, acc1[u]);
+            else { st(dK + o, acc1[u]); st(dV + o, acc2[u]); }
+        }
+    }
+}
+
+template <typename T, int D>
+hipError_t softmax_bwd_generic_TD(const Geom& g, const T* Q, const T* K, const T* V, const T* dO,
+                                  const float* LSE, const float* delta, T* dQ, T* dK, T* dV, int causal,
+                                  hipStream_t st)
+{
+    dim3 grid((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
+    hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 0>), grid, block, 0, st, g, Q, K, V, dO, LSE, delta,
+                       dQ, dK, dV, causal);
+    hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 1>), grid, block, 0, st, g, Q, K, V, dO, LSE, delta,
+                       dQ, dK, dV, causal);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t softmax_bwd_generic_T(const Geom& g, const T* Q, const T* K, const T* V, const T* dO,
+                                 const float* LSE, const float* delta, T* dQ, T* dK, T* dV, int causal,
+                                 hipStream_t st)
+{
+    switch (g.d) {
+        case 16: return softmax_bwd_generic_TD<T, 16>(g, Q, K, V, dO, LSE, delta, dQ, dK, dV, causal, st);
+        case 32: return softmax_bwd_generic_TD<T, 32>(g, Q, K, V, dO, LSE, delta, dQ, dK, dV, causal, st);
+        case 64: return softmax_bwd_generic_TD<T, 64>(g, Q, K, V, dO, LSE, delta, dQ, dK, dV, causal, st);
+        default: return softmax_bwd_generic_TD<T, 128>(g, Q, K, V, dO, LSE, delta, dQ, dK, dV, causal, st);
+    }
+}
+
 template <typename T>
 hipError_t states_generic_T(const Geom& g, const T* K, const T* V, float* M, int anchor, hipStream_t st)
 {
@@ -508,6 +648,35 @@ hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, c
                                  static_cast<const __hip_bfloat16*>(K),
                                  static_cast<const __hip_bfloat16*>(V), static_cast<__hip_bfloat16*>(O),
                                  LSE, causal, st);
+}
+
+hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, float* delta,
+                                hipStream_t st)
+{
+    const size_t rows = (size_t)g.G * (size_t)g.N;
+    dim3 grid((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64))), block(kThreads);
+    if (dtype == LASP2_F32)
+        hipLaunchKernelGGL(softmax_delta_kernel<float>, grid, block, 0, st, g, static_cast<const float*>(O),
+                           static_cast<const float*>(dO), delta);
+    else
+        hipLaunchKernelGGL(softmax_delta_kernel<__hip_bfloat16>, grid, block, 0, st, g,
+                           static_cast<const __hip_bfloat16*>(O), static_cast<const __hip_bfloat16*>(dO), delta);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_bwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
+                                      const void* V, const void* dO, const float* LSE, const float* delta,
+                                      void* dQ, void* dK, void* dV, int causal, hipStream_t st)
+{
+    if (dtype == LASP2_F32)
+        return softmax_bwd_generic_T(g, static_cast<const float*>(Q), static_cast<const float*>(K),
+                                     static_cast<const float*>(V), static_cast<const float*>(dO), LSE, delta,
+                                     static_cast<float*>(dQ), static_cast<float*>(dK), static_cast<float*>(dV),
+                                     causal, st);
+    typedef __hip_bfloat16 bf;
+    return softmax_bwd_generic_T(g, static_cast<const bf*>(Q), static_cast<const bf*>(K),
+                                 static_cast<const bf*>(V), static_cast<const bf*>(dO), LSE, delta,
+                                 static_cast<bf*>(dQ), static_cast<bf*>(dK), static_cast<bf*>(dV), causal, st);
 }
 
 hipError_t launch_state_total(const Geom& g, const float* M, float* S, hipStream_t st)

@@ -290,6 +290,38 @@ int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, co
     return from_hip(launch_softmax_fwd_generic(g, desc->dtype, Q, K, V, O, LSE, causal ? 1 : 0, st));
 }
 
+int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
+{
+    if (!bytes) return LASP2_ERR_NULL;
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    *bytes = (size_t)g.G * (size_t)g.N * sizeof(float);
+    return LASP2_OK;
+}
+
+int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                      const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                      void* workspace, size_t workspace_bytes, int causal, void* stream)
+{
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    if (g.decay) return LASP2_ERR_DECAY;
+    if (empty) return LASP2_OK;
+    rc = check_ptrs({Q, K, V, O, dO, LSE, dQ, dK, dV, workspace});
+    if (rc != LASP2_OK) return rc;
+    if (workspace_bytes < (size_t)g.G * (size_t)g.N * sizeof(float)) return LASP2_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float* delta = static_cast<float*>(workspace);
+    hipError_t e = launch_softmax_delta(g, desc->dtype, O, dO, delta, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    return from_hip(launch_softmax_bwd_generic(g, desc->dtype, Q, K, V, dO, LSE, delta, dQ, dK, dV,
+                                               causal ? 1 : 0, st));
+}
+
 const char* lasp2_status_string(int status)
 {
     switch (status) {

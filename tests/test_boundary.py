@@ -33,7 +33,8 @@ def test_header_symbols_are_exported():
     names = set(re.findall(r"\b(lasp2_[a-z0-9_]+)\s*\(", text))
     assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
             "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string", "lasp2_state_total",
-            "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd"} <= names
+            "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd", "lasp2_softmax_bwd",
+            "lasp2_softmax_workspace_size"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lasp2.h but not exported"
@@ -124,6 +125,12 @@ def test_null_and_alignment_errors_reach_no_device():
         a = [FAKE] * 5; a[i] = None
         assert lib.lasp2_softmax_fwd(r, *a, 1, None) == -1
     assert lib.lasp2_softmax_fwd(r, FAKE, FAKE, ODD, FAKE, FAKE, 0, None) == -6
+    sneed = ctypes.c_size_t(0)
+    assert lib.lasp2_softmax_workspace_size(r, ctypes.byref(sneed)) == 0 and sneed.value == 1 * 2 * 1024 * 4
+    for i in range(10):
+        a = [FAKE] * 10; a[i] = None
+        assert lib.lasp2_softmax_bwd(r, *a, ctypes.c_size_t(1 << 40), 1, None) == -1
+    assert lib.lasp2_softmax_bwd(r, *([FAKE] * 10), ctypes.c_size_t(sneed.value - 1), 1, None) == -5
 
 
 def test_decay_errors():
@@ -156,3 +163,4 @@ def test_empty_problem_is_ok_without_pointers():
         assert lib.lasp2_nomask_fwd(r, None, None, None, None) == 0
         assert lib.lasp2_nomask_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0
         assert lib.lasp2_softmax_fwd(r, *([None] * 5), 0, None) == 0
+        assert lib.lasp2_softmax_bwd(r, *([None] * 10), ctypes.c_size_t(0), 0, None) == 0

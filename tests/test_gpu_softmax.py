@@ -1,4 +1,4 @@
-"""GPU parity of lasp2_softmax_fwd (softmax attention over gathered keys and values) against the
+"""GPU parity of lasp2_softmax_fwd / lasp2_softmax_bwd (softmax attention over gathered keys and values) against the
 CPU oracle, element by element on seeded inputs: fp32 and bf16, with and without the causal
 mask, query counts that are not multiples of any tile, packed documents."""
 import numpy as np
@@ -29,9 +29,24 @@ def _run(oracle, B, H, N, d, dtype, seed, causal, cu=None, scale_inputs=1.0):
     O_ref, lse_ref = oracle.softmax_fwd(x64["Q"], x64["K"], x64["V"], causal, cu)
     eo = rel_l2(to_host(O), O_ref)
     el = float(np.abs(LSE.cpu().numpy().reshape(G, N).astype(np.float64) - lse_ref).max())
-    print({"O": f"{eo:.2e}", "lse_abs": f"{el:.2e}"}, flush=True)
+    # backward from the forward's own O and LSE
+    dOh = synth.gen_tensor(seed, "dO", G, N, d, dtype)
+    dO = to_device(dOh, B, H, dtype)
+    dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+    ws = torch.empty(bd.lasp2_softmax_workspace_size(p) // 4, dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_bwd(p, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, causal)
+    torch.cuda.synchronize()
+    refs = oracle.softmax_bwd(x64["Q"], x64["K"], x64["V"], dOh.astype(np.float64), causal, cu)
+    # a single key per row makes dQ and dK exactly zero: measure those against the scale of dV
+    floor = max(np.linalg.norm(refs[2]), 1e-300)
+    eg = {n: (rel_l2(to_host(t), r) if np.linalg.norm(r) > 1e-9 * floor
+              else float(np.linalg.norm(to_host(t)) / floor))
+          for n, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs)}
+    print({"O": f"{eo:.2e}", "lse_abs": f"{el:.2e}", **{k: f"{v:.2e}" for k, v in eg.items()}}, flush=True)
     assert eo <= TOL[dtype], (eo, el)
     assert el <= (1e-4 if dtype == "f32" else 2e-2), (eo, el)
+    for k, v in eg.items():
+        assert v <= TOL[dtype], (k, eg)
 
 
 @pytest.mark.parametrize("causal", [False, True])
