@@ -551,10 +551,12 @@ hipError_t softmax_bwd_generic_TD(const Geom& g, const T* Q, const T* K, const T
                                   hipStream_t st)
 {
     dim3 grid((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
-    hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 0>), grid, block, 0, st, g, Q, K, V, dO, LSE, delta,
-                       dQ, dK, dV, causal);
-    hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 1>), grid, block, 0, st, g, Q, K, V, dO, LSE, delta,
-                       dQ, dK, dV, causal);
+    if (dQ)
+        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 0>), grid, block, 0, st, g, Q, K, V, dO, LSE,
+                           delta, dQ, dK, dV, causal);
+    if (dK)
+        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 1>), grid, block, 0, st, g, Q, K, V, dO, LSE,
+                           delta, dQ, dK, dV, causal);
     return hipGetLastError();
 }
 

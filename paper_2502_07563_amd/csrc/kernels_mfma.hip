@@ -1410,6 +1410,435 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     }
 }
 
+// =====================================================================================
+// Softmax attention backward, dQ: the forward's walk again (one workgroup per 256 queries, keys
+// and values streamed), with the probabilities rebuilt from the stored log-sum-exp instead of
+// an online maximum:  P = exp(s - lse_i), dP = V_tile dO_w^T, dS = P (dP - delta_i) / sqrt(d),
+// dQ^T += K_tile^T dS.  Everything per query is per lane, as in the forward.
+// =====================================================================================
+__global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
+    Geom g, const char* __restrict__ Q, const char* __restrict__ K, const char* __restrict__ V,
+    const char* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    char* __restrict__ dQ, int causal, float scale_log2e, float scale)
+{
+    constexpr int NW = SM_NW, DPS = 2 * (16 / NW);
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sK = smem;
+    char* sV = smem + NSTAGE * STAGE_BYTES;
+    char* sO = smem + 2 * NSTAGE * STAGE_BYTES;   // output staging, 4 KiB per wave
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, l32 = lane & 31;
+    const int nqb = (g.N + SM_QB - 1) / SM_QB;
+    const unsigned units = (unsigned)g.G * (unsigned)nqb;
+    const unsigned per_xcd = (units + 7u) / 8u;
+    const unsigned unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || unit >= units) return;
+    const int grp = (int)(unit / (unsigned)nqb);
+    const int qb = nqb - 1 - (int)(unit % (unsigned)nqb);
+    const int r0 = qb * SM_QB;
+    const int rlast = min(r0 + SM_QB, g.N) - 1;
+    const size_t base = (size_t)grp * g.N * ROWB;
+
+    int blo, bhi, tmp;
+    doc_range(g, r0, blo, tmp);
+    doc_range(g, rlast, tmp, bhi);
+    if (causal) bhi = rlast + 1;
+    const int qi = r0 + 32 * w + l32;
+    const bool valid = qi < g.N;
+    int lo_i = 0, hi_i = 0;
+    if (valid) {
+        doc_range(g, qi, lo_i, hi_i);
+        if (causal) hi_i = qi + 1;
+    }
+    const int lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? lo_i : g.N));
+    const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_i : 0));
+    const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_i : g.N));
+    const int hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? hi_i : 0));
+
+    const int kb0 = blo / KB, kb1 = (bhi + KB - 1) / KB;
+    const int NBK = kb1 - kb0;
+    uint32_t dvo[16 / NW];
+#pragma unroll
+    for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
+    auto issue = [&](int i) {
+        dma_block<NW>(K, V, base, (kb0 + i) * KB, g.N, sK + (i % NSTAGE) * STAGE_BYTES,
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, lane, dvo);
+    };
+    issue(0);
+    if (NBK > 1) issue(1);
+
+    // lane offsets of the natural and the transposed reads; the other k-steps and column blocks
+    // differ from these only in address bits 5..7, which the row term leaves clear, so they are
+    // derived with one XOR at the point of use instead of being held in registers
+    const int nat0 = tile_off(l32, h);
+    int pv0, pv1;
+    {
+        const int i = lane & 15, g2 = (lane >> 4) & 1;
+        const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
+        pv0 = tr_off(4 * h + rl, cl);
+        pv1 = tr_off(8 + 4 * h + rl, cl);
+    }
+#define NAT(ks) (nat0 ^ ((ks) << 5))
+#define PV0(tv) (pv0 ^ ((tv) << 6))
+#define PV1(tv) (pv1 ^ ((tv) << 6))
+
+    // this wave's 32 queries and their dO rows as B-operand fragments; zero past the end
+    bf16x8 qf[8], gf[8];
+    {
+        const size_t ro = base + (size_t)min(qi, g.N - 1) * ROWB + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            const u32x4 x = *reinterpret_cast<const u32x4*>(Q + ro + 32 * ks);
+            const u32x4 y = *reinterpret_cast<const u32x4*>(dO + ro + 32 * ks);
+            qf[ks] = __builtin_bit_cast(bf16x8, valid ? x : z);
+            gf[ks] = __builtin_bit_cast(bf16x8, valid ? y : z);
+        }
+    }
+    const size_t li = (size_t)grp * g.N + min(qi, g.N - 1);
+    const float lse2 = LSE[li] * 1.4426950408889634f;   // log2 of the row's sum of exponentials
+    const float dlt = delta[li];
+
+    f32x16 Oacc[4];
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+
+    for (int bi = 0; bi < NBK; ++bi) {
+        char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
+        char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+        const int k0b = (kb0 + bi) * KB;
+        if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+        if (k0b + KB > g.N) zero_tail_rows<NW>(k0b, g.N, tK, tV, w, lane);
+        __syncthreads();
+        if (bi + 2 < NBK) issue(bi + 2);
+
+        bf16x8 bufA[4], bufB[4];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int k0 = k0b + 32 * half;
+            if (k0 >= hi_max || k0 + 32 <= lo_min) continue;
+            const bool whole = (k0 >= lo_max) && (k0 + 32 <= hi_min);
+            const char* tKh = tK + half * (32 * ROWB);
+            const char* tVh = tV + half * (32 * ROWB);
+            // scores^T = K_tile Q_w^T and dP^T = V_tile dO_w^T (keys x queries)
+            f32x16 sc, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tKh, NAT(ks));
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tKh, NAT(ks + 4));
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tVh, NAT(ks));
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tVh, NAT(ks + 4));
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) dp = mfma(bufA[ks], gf[ks], dp);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) bufA[tv] = lds_read_tr8_at(tKh, PV0(tv), PV1(tv));
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) dp = mfma(bufB[ks], gf[ks + 4], dp);
+            SCHED_FENCE();
+            // dS = P (dP - delta) / sqrt(d), P = exp2(scale_log2e s - lse2); zero outside the mask
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = k0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                const bool keep = whole || (key >= lo_i && key < hi_i);
+                const float p = exp2f(fmaf(sc[v], scale_log2e, -lse2));
+                sc[v] = keep ? p * (dp[v] - dlt) * scale : 0.f;
+            }
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) bufB[tv] = lds_read_tr8_at(tKh + 16 * ROWB, PV0(tv), PV1(tv));
+            SCHED_FENCE();
+            {
+                u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
+            }
+            {
+                u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+            }
+            SCHED_FENCE();
+        }
+    }
+
+    {
+        char* stg = sO + w * 4096;
+        const int rbase = r0 + 32 * w;
+#pragma unroll
+        for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+            for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16& o = Oacc[2 * hv + tvv];
+                    u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                    *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                if (rbase + row < g.N)
+                    *reinterpret_cast<u32x4*>(dQ + base + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+            }
+        }
+    }
+}
+#undef NAT
+#undef PV0
+#undef PV1
+
+// =====================================================================================
+// Softmax attention backward, dK and dV: one workgroup of four waves per 128 keys (32 per wave,
+// one per lane), queries and their dO rows streamed in 64-token stages together with each
+// query's log-sum-exp and delta.  With scores laid out queries x keys, every per-key quantity
+// (mask bounds, the K and V rows as B operands, the two accumulators' columns) is per lane:
+//   S = Q_tile K_w^T, dP = dO_tile V_w^T, P = exp(S/sqrt(d) - lse), dS = P (dP - delta)/sqrt(d),
+//   dV^T += dO_tile^T P,  dK^T += Q_tile^T dS.
+// Four waves, one per SIMD, so that a wave may hold both accumulators and both operand sets
+// (about 330 registers, the upper part in the accumulation file).
+// =====================================================================================
+constexpr int SK_NW = 4, SK_KB = SK_NW * 32;
+
+__device__ __forceinline__ void dma4(const char* sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+
+__global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
+    Geom g, const char* __restrict__ Q, const char* __restrict__ K, const char* __restrict__ V,
+    const char* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    char* __restrict__ dK, char* __restrict__ dV, int causal, float scale_log2e, float scale)
+{
+    constexpr int NW = SK_NW, DPS = 2 * (16 / NW) + 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sQ = smem;
+    char* sG = smem + NSTAGE * STAGE_BYTES;
+    char* sL = smem + 2 * NSTAGE * STAGE_BYTES;   // per stage: 64 lse, then 64 delta (512 bytes)
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, l32 = lane & 31;
+    const int nkb = (g.N + SK_KB - 1) / SK_KB;
+    const unsigned units = (unsigned)g.G * (unsigned)nkb;
+    const unsigned per_xcd = (units + 7u) / 8u;
+    const unsigned unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || unit >= units) return;
+    const int grp = (int)(unit / (unsigned)nkb);
+    const int kb = (int)(unit % (unsigned)nkb);     // causal: the first key blocks see the most queries
+    const int c0 = kb * SK_KB;
+    const int clast = min(c0 + SK_KB, g.N) - 1;
+    const size_t base = (size_t)grp * g.N * ROWB;
+
+    // queries this workgroup must visit, and per key (lane) the queries that attend to it
+    int blo, bhi, tmp;
+    doc_range(g, c0, blo, tmp);
+    doc_range(g, clast, tmp, bhi);
+    if (causal) blo = c0;
+    const int kj = c0 + 32 * w + l32;
+    const bool valid = kj < g.N;
+    int lo_j = 0, hi_j = 0;
+    if (valid) {
+        doc_range(g, kj, lo_j, hi_j);
+        if (causal) lo_j = kj;
+    }
+    const int lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? lo_j : g.N));
+    const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_j : 0));
+    const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_j : g.N));
+    const int hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? hi_j : 0));
+
+    const int qb0 = blo / KB, qb1 = (bhi + KB - 1) / KB;
+    const int NBK = qb1 - qb0;
+    uint32_t dvo[16 / NW];
+#pragma unroll
+    for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
+    const char* lse_g = reinterpret_cast<const char*>(LSE + (size_t)grp * g.N);
+    const char* dlt_g = reinterpret_cast<const char*>(delta + (size_t)grp * g.N);
+    auto issue = [&](int i) {
+        const int st = i % NSTAGE, q0 = (qb0 + i) * KB;
+        dma_block<NW>(Q, dO, base, q0, g.N, sQ + st * STAGE_BYTES, sG + st * STAGE_BYTES, w, lane, dvo);
+        // every wave fetches the stage's 64 lse and 64 delta values (the same bytes to the same
+        // place), which keeps the number of loads in flight equal across waves
+        const uint32_t vo = 4u * (uint32_t)min(q0 + lane, g.N - 1);
+        dma4(lse_g, vo, lds_addr_of(sL + st * 512));
+        dma4(dlt_g, vo, lds_addr_of(sL + st * 512 + 256));
+    };
+    issue(0);
+    if (NBK > 1) issue(1);
+
+    const int nat0 = tile_off(l32, h);
+    int pv0, pv1;
+    {
+        const int i = lane & 15, g2 = (lane >> 4) & 1;
+        const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
+        pv0 = tr_off(4 * h + rl, cl);
+        pv1 = tr_off(8 + 4 * h + rl, cl);
+    }
+#define NAT(ks) (nat0 ^ ((ks) << 5))
+#define PV0(tv) (pv0 ^ ((tv) << 6))
+#define PV1(tv) (pv1 ^ ((tv) << 6))
+
+    // this wave's 32 keys: K and V rows as B-operand fragments; zero past the end
+    bf16x8 kf[8], vf[8];
+    {
+        const size_t ro = base + (size_t)min(kj, g.N - 1) * ROWB + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            const u32x4 x = *reinterpret_cast<const u32x4*>(K + ro + 32 * ks);
+            const u32x4 y = *reinterpret_cast<const u32x4*>(V + ro + 32 * ks);
+            kf[ks] = __builtin_bit_cast(bf16x8, valid ? x : z);
+            vf[ks] = __builtin_bit_cast(bf16x8, valid ? y : z);
+        }
+    }
+
+    f32x16 Kacc[4], Vacc[4];
+#pragma unroll
+    for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { Kacc[tv][v] = 0.f; Vacc[tv][v] = 0.f; }
+
+    for (int bi = 0; bi < NBK; ++bi) {
+        const int st = bi % NSTAGE;
+        char* tQ = sQ + st * STAGE_BYTES;
+        char* tG = sG + st * STAGE_BYTES;
+        const char* tL = sL + st * 512;
+        const int q0b = (qb0 + bi) * KB;
+        if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+        if (q0b + KB > g.N) zero_tail_rows<NW>(q0b, g.N, tQ, tG, w, lane);
+        __syncthreads();
+        if (bi + 2 < NBK) issue(bi + 2);
+
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int q0 = q0b + 32 * half;
+            if (q0 >= hi_max || q0 + 32 <= lo_min) continue;
+            const bool whole = (q0 >= lo_max) && (q0 + 32 <= hi_min);
+            const char* tQh = tQ + half * (32 * ROWB);
+            const char* tGh = tG + half * (32 * ROWB);
+            bf16x8 bufQ[8], bufG[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) bufQ[ks] = lds_read16_at(tQh, NAT(ks));
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) bufG[ks] = lds_read16_at(tGh, NAT(ks));
+            // the queries of this lane's 16 result rows: 8 (v/4) + 4 h + v%4
+            f32x4 ls[4], dl[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                ls[q] = *reinterpret_cast<const f32x4*>(tL + (32 * half + 8 * q + 4 * h) * 4);
+                dl[q] = *reinterpret_cast<const f32x4*>(tL + 256 + (32 * half + 8 * q + 4 * h) * 4);
+            }
+            SCHED_FENCE();
+            f32x16 sc, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) sc = mfma(bufQ[ks], kf[ks], sc);
+            SCHED_FENCE();
+            // transposed operands of the two accumulations, fetched under the dP products
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) {
+                bufQ[tv] = lds_read_tr8_at(tQh, PV0(tv), PV1(tv));
+                bufQ[4 + tv] = lds_read_tr8_at(tQh + 16 * ROWB, PV0(tv), PV1(tv));
+            }
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) dp = mfma(bufG[ks], vf[ks], dp);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) {
+                bufG[tv] = lds_read_tr8_at(tGh, PV0(tv), PV1(tv));
+                bufG[4 + tv] = lds_read_tr8_at(tGh + 16 * ROWB, PV0(tv), PV1(tv));
+            }
+            SCHED_FENCE();
+            // P and dS in place of the scores and dP; zero outside the mask
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                const bool keep = whole || (qi >= lo_j && qi < hi_j);
+                const float pr = exp2f(fmaf(sc[v], scale_log2e, -1.4426950408889634f * ls[v >> 2][v & 3]));
+                sc[v] = keep ? pr : 0.f;
+                dp[v] = keep ? pr * (dp[v] - dl[v >> 2][v & 3]) * scale : 0.f;
+            }
+            {
+                u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
+                u32x4 dk = {pack2(dp[0], dp[1]), pack2(dp[2], dp[3]), pack2(dp[4], dp[5]), pack2(dp[6], dp[7])};
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk), db = __builtin_bit_cast(bf16x8, dk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) {
+                    Vacc[tv] = mfma(bufG[tv], pb, Vacc[tv]);
+                    Kacc[tv] = mfma(bufQ[tv], db, Kacc[tv]);
+                }
+            }
+            {
+                u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                u32x4 dk = {pack2(dp[8], dp[9]), pack2(dp[10], dp[11]), pack2(dp[12], dp[13]), pack2(dp[14], dp[15])};
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk), db = __builtin_bit_cast(bf16x8, dk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) {
+                    Vacc[tv] = mfma(bufG[4 + tv], pb, Vacc[tv]);
+                    Kacc[tv] = mfma(bufQ[4 + tv], db, Kacc[tv]);
+                }
+            }
+            SCHED_FENCE();
+        }
+    }
+
+    // dK^T and dV^T (d x keys) -> rows of dK, dV through a 4 KiB per-wave staging area that
+    // reuses the first stage (all waves are past their last tile read after the barrier)
+    __syncthreads();
+    {
+        char* stg = smem + w * 4096;
+        const int rbase = c0 + 32 * w;
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            char* out = which ? dV : dK;
+#pragma unroll
+            for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+                for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16& o = which ? Vacc[2 * hv + tvv] : Kacc[2 * hv + tvv];
+                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                        *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
+                    if (rbase + row < g.N)
+                        *reinterpret_cast<u32x4*>(out + base + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                }
+            }
+        }
+    }
+#undef NAT
+#undef PV0
+#undef PV1
+}
+
 }  // namespace
 
 bool mfma_path_supported(const Geom& g, int dtype)
@@ -1494,6 +1923,45 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
 }
 
 bool softmax_mfma_supported(const Geom& g, int dtype) { return dtype == LASP2_BF16 && g.d == D; }
+
+hipError_t launch_softmax_bwd_dkv_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                       const void* dO, const float* LSE, const float* delta, void* dK,
+                                       void* dV, int causal, hipStream_t st)
+{
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + NSTAGE * 512;   // 97.5 KiB
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_bwd_dkv_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned nkb = ((unsigned)g.N + SK_KB - 1) / SK_KB;
+    const unsigned units = (unsigned)g.G * nkb;
+    const unsigned gx = 8u * ((units + 7u) / 8u);
+    const float scale = 1.f / sqrtf((float)g.d);
+    hipLaunchKernelGGL(softmax_bwd_dkv_mfma_kernel, dim3(gx), dim3(SK_NW * 64), smem, st, g,
+                       static_cast<const char*>(Q), static_cast<const char*>(K),
+                       static_cast<const char*>(V), static_cast<const char*>(dO), LSE, delta,
+                       static_cast<char*>(dK), static_cast<char*>(dV), causal,
+                       1.4426950408889634f * scale, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_bwd_dq_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                      const void* dO, const float* LSE, const float* delta, void* dQ,
+                                      int causal, hipStream_t st)
+{
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + SM_NW * 4096;   // 128 KiB
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_bwd_dq_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned nqb = ((unsigned)g.N + SM_QB - 1) / SM_QB;
+    const unsigned units = (unsigned)g.G * nqb;
+    const unsigned gx = 8u * ((units + 7u) / 8u);
+    const float scale = 1.f / sqrtf((float)g.d);
+    hipLaunchKernelGGL(softmax_bwd_dq_mfma_kernel, dim3(gx), dim3(SM_NW * 64), smem, st, g,
+                       static_cast<const char*>(Q), static_cast<const char*>(K),
+                       static_cast<const char*>(V), static_cast<const char*>(dO), LSE, delta,
+                       static_cast<char*>(dQ), causal, 1.4426950408889634f * scale, scale);
+    return hipGetLastError();
+}
 
 hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V, void* O,
                                    float* LSE, int causal, hipStream_t st)

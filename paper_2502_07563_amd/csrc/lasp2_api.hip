@@ -318,6 +318,11 @@ int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, co
     float* delta = static_cast<float*>(workspace);
     hipError_t e = launch_softmax_delta(g, desc->dtype, O, dO, delta, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    if (softmax_mfma_supported(g, desc->dtype)) {
+        e = launch_softmax_bwd_dq_mfma(g, Q, K, V, dO, LSE, delta, dQ, causal ? 1 : 0, st);
+        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+        return from_hip(launch_softmax_bwd_dkv_mfma(g, Q, K, V, dO, LSE, delta, dK, dV, causal ? 1 : 0, st));
+    }
     return from_hip(launch_softmax_bwd_generic(g, desc->dtype, Q, K, V, dO, LSE, delta, dQ, dK, dV,
                                                causal ? 1 : 0, st));
 }

@@ -113,10 +113,17 @@ hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, c
 // delta[g][i] = dO_i . O_i, then dQ, dK, dV of softmax attention from Q, K, V, dO, LSE, delta.
 hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, float* delta,
                                 hipStream_t st);
+// (dQ == NULL: only dK, dV are computed; dK == NULL: only dQ)
 hipError_t launch_softmax_bwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
                                       const void* V, const void* dO, const float* LSE, const float* delta,
                                       void* dQ, void* dK, void* dV, int causal, hipStream_t st);
 bool softmax_mfma_supported(const Geom& g, int dtype);
+hipError_t launch_softmax_bwd_dq_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                      const void* dO, const float* LSE, const float* delta, void* dQ,
+                                      int causal, hipStream_t st);
+hipError_t launch_softmax_bwd_dkv_mfma(const Geom& g, const void* Q, const void* K, const void* V,
+                                       const void* dO, const float* LSE, const float* delta, void* dK,
+                                       void* dV, int causal, hipStream_t st);
 hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V, void* O,
                                    float* LSE, int causal, hipStream_t st);
 
