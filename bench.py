@@ -55,6 +55,80 @@ def cpu_baseline(cfg, sample_tokens):
                       f"of the workload, {dt:.1f} s"}
 
 
+def softmax_main(args):
+    """The standard-attention layer of the hybrid model (forward + backward of
+    lasp2_softmax_fwd / lasp2_softmax_bwd), causal, at B=1, H=16, N=32768, d=128: one rank's
+    share when a sequence of that length sits on one GPU.  Priced against the bf16 MFMA peak with
+    the algorithmic flop count on the causal triangle: 2 products forward, 5 backward."""
+    import numpy as np
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    B, H, N, d = 1, 16, args.softmax_len, 128
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = bd.Problem(B, H, N, d, 64, 0, "bf16")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(41)
+    mk = lambda: torch.randn((B, H, N, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    Q, K, V, dO = mk(), mk(), mk(), mk()
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    LSE = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(bd.lasp2_softmax_workspace_size(p), dtype=torch.uint8, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        e = [ev() for _ in range(3)] if record else None
+        if record:
+            e[0].record()
+        bd.lasp2_softmax_fwd(p, Q, K, V, O, LSE, True)
+        if record:
+            e[1].record()
+        bd.lasp2_softmax_bwd(p, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, True)
+        if record:
+            e[2].record()
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    t_fwd = sum(m[0].elapsed_time(m[1]) for m in marks) / len(marks)
+    t_bwd = sum(m[1].elapsed_time(m[2]) for m in marks) / len(marks)
+    pairs = B * H * N * (N + 1) / 2.0          # (query, key) pairs inside the causal mask
+    fl_fwd, fl_bwd = 4.0 * pairs * d, 10.0 * pairs * d
+    out = {
+        "metric": "fwd+bwd tokens/s per layer", "value": B * N / (dt / args.steps), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"softmax attention layer of the hybrid model: B={B} H={H} N={N} d={d} causal"},
+        "ms": {"softmax_fwd": t_fwd, "softmax_bwd": t_bwd},
+        "roofline": {"bound": "mfma", "kernel": "lasp2_softmax_bwd (delta, dQ and dK/dV kernels; the dK/dV "
+                     "kernel dominates)", "achieved": fl_bwd / (t_bwd * 1e-3) / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": fl_bwd / (t_bwd * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "fwd_TFLOPs": fl_fwd / (t_fwd * 1e-3) / 1e12,
+                     "fwd_frac": fl_fwd / (t_fwd * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(N, 4096)
+        rng = np.random.default_rng(41)
+        x = [rng.standard_normal((H, n, d)) for _ in range(4)]
+        t0 = time.perf_counter()
+        oracle.softmax_fwd(x[0], x[1], x[2], True)
+        oracle.softmax_bwd(x[0], x[1], x[2], x[3], True)
+        dtc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n / dtc, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"fp64 oracle, softmax fwd+bwd, {H} heads x {n} tokens (the rate falls "
+                                         f"as 1/N; at N={N} it would be about {n / dtc * n / N:.1f}), {dtc:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +141,10 @@ def main():
     ap.add_argument("--decay", action="store_true",
                     help="run the step with scalar decay, per-head factors 1 - 2^(-5-h) (not the headline "
                          "workload; the CPU baseline, which is the undecayed oracle, is then left out)")
+    ap.add_argument("--softmax", action="store_true",
+                    help="time the standard-attention layer of the hybrid model instead (not the headline "
+                         "workload): causal softmax attention forward + backward, B=1 H=16 d=128")
+    ap.add_argument("--softmax-len", type=int, default=32768, help="sequence length for --softmax")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -77,6 +155,9 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.softmax:
+        return softmax_main(args)
 
     import torch
     from paper_2502_07563_amd import binding as bd

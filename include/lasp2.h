@@ -227,7 +227,7 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
 int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                       const void* V, void* O, float* LSE, int causal, void* stream);
 
-/* Bytes of device scratch lasp2_softmax_bwd needs (one fp32 per query row). */
+/* Bytes of device scratch lasp2_softmax_bwd needs (two fp32 per query row). */
 int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
 
 /*
@@ -238,7 +238,10 @@ int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
  *   dV = P^T dO.
  * In: Q,K,V,O,dO [B,H,N,d]; LSE [B,H,N] from the forward; same `causal`.
  * Out: dQ,dK,dV [B,H,N,d].  `workspace`: device scratch of at least
- * lasp2_softmax_workspace_size() bytes, 16-byte aligned (receives delta).
+ * lasp2_softmax_workspace_size() bytes, 16-byte aligned (receives delta and
+ * the log-sum-exp in base 2).
+ * bf16 with d = 128 runs on the matrix cores (one kernel for dQ, one for dK
+ * and dV), everything else on plain fp32 kernels.
  */
 int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                       const void* V, const void* O, const void* dO, const float* LSE,

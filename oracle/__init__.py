@@ -470,3 +470,18 @@ def softmax_rows(Q, K, V, rows, causal=False, cu=None):
                                      ctypes.c_int(1 if causal else 0), out.ctypes.data_as(_c_dp),
                                      lse.ctypes.data_as(_c_dp))
     return out, lse
+
+def softmax_bwd_rows(Q, K, V, dO, lse, delta, rows, which, causal=False, cu=None):
+    """Rows `rows` of dQ (which=0), dK (1) or dV (2) for ONE group; Q,K,V,dO are [N, d]; lse and
+    delta = rowsum(dO * O) are this oracle's own forward results for all N rows of the group."""
+    N, d = Q.shape
+    Q, q = _d(Q); K, k = _d(K); V, v = _d(V); dO, g = _d(dO)
+    lse, l = _d(lse); delta, dl = _d(delta)
+    rows, r = _l(rows)
+    out = np.empty((len(rows), d))
+    cu, c = _l(_cu(cu, N))
+    _lib().lasp2_oracle_softmax_bwd_rows(q, k, v, g, l, dl, ctypes.c_long(N), ctypes.c_long(d), c,
+                                         ctypes.c_long(len(cu) - 1), r, ctypes.c_long(len(rows)),
+                                         ctypes.c_int(which), ctypes.c_int(1 if causal else 0),
+                                         out.ctypes.data_as(_c_dp))
+    return out

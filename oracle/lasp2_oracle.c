@@ -1032,3 +1032,46 @@ void lasp2_oracle_softmax_rows(const double* Q, const double* K, const double* V
     }
     free(doc);
 }
+
+/*
+ * Selected rows of dQ (which = 0), dK (1) or dV (2) of the softmax gradient above, one group;
+ * Q, K, V, dO are [N][d].  lse[i] and delta[i] = dO_i . O_i come from this oracle's own forward
+ * over the whole group; with them P_ij = exp(scale q_i . k_j - lse_i) needs no further row sums,
+ * which is what makes single rows of dK and dV (sums over all queries) affordable at sizes
+ * where the full gradient is not.
+ */
+void lasp2_oracle_softmax_bwd_rows(const double* Q, const double* K, const double* V,
+                                   const double* dO, const double* lse, const double* delta,
+                                   long N, long d, const long* cu, long n_docs, const long* rows,
+                                   long n_rows, int which, int causal, double* out)
+{
+    long* doc = doc_ids(N, cu, n_docs);
+    double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < n_rows; ++r) {
+        long t = rows[r];
+        long dlo = cu[doc[t]], dhi = cu[doc[t] + 1];
+        double* o = out + r * d;
+        for (long a = 0; a < d; ++a) o[a] = 0.0;
+        if (which == 0) {
+            long hi = causal ? t + 1 : dhi;
+            for (long j = dlo; j < hi; ++j) {
+                double p = exp(scale * dot(Q + t * d, K + j * d, d) - lse[t]);
+                double ds = p * (dot(dO + t * d, V + j * d, d) - delta[t]);
+                for (long a = 0; a < d; ++a) o[a] += scale * ds * K[j * d + a];
+            }
+        } else {
+            long lo = causal ? t : dlo;
+            for (long i = lo; i < dhi; ++i) {
+                double p = exp(scale * dot(Q + i * d, K + t * d, d) - lse[i]);
+                if (which == 1) {
+                    double ds = p * (dot(dO + i * d, V + t * d, d) - delta[i]);
+                    for (long a = 0; a < d; ++a) o[a] += scale * ds * Q[i * d + a];
+                } else {
+                    for (long a = 0; a < d; ++a) o[a] += p * dO[i * d + a];
+                }
+            }
+        }
+    }
+    free(doc);
+}

@@ -432,11 +432,14 @@ hipError_t softmax_fwd_generic_T(const Geom& g, const T* Q, const T* K, const T*
 }
 
 // delta_i = dO_i . O_i for every row (the row sums the softmax backward needs); one wave-sized
-// group of 64 threads per row.
+// group of 64 threads per row.  lse2, when given, receives the row's log-sum-exp times log2(e),
+// the form in which the matrix-core dK/dV kernel subtracts it from base-2 scores.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void softmax_delta_kernel(Geom g, const T* __restrict__ O,
                                                                  const T* __restrict__ dO,
-                                                                 float* __restrict__ delta)
+                                                                 const float* __restrict__ LSE,
+                                                                 float* __restrict__ delta,
+                                                                 float* __restrict__ lse2)
 {
     const size_t rows = (size_t)g.G * (size_t)g.N;
     const size_t row = (size_t)blockIdx.x * (kThreads / 64) + threadIdx.x / 64;
@@ -446,7 +449,10 @@ __global__ __launch_bounds__(kThreads) void softmax_delta_kernel(Geom g, const T
     for (int a = lane; a < g.d; a += 64) acc = fmaf(ld(O + row * g.d + a), ld(dO + row * g.d + a), acc);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (lane == 0) delta[row] = acc;
+    if (lane == 0) {
+        delta[row] = acc;
+        if (lse2) lse2[row] = LSE[row] * 1.4426950408889634f;
+    }
 }
 
 // Softmax attention backward, plain fp32, in two kernels that mirror the forward one.
@@ -652,17 +658,18 @@ hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, c
                                  LSE, causal, st);
 }
 
-hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, float* delta,
-                                hipStream_t st)
+hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, const float* LSE,
+                                float* delta, float* lse2, hipStream_t st)
 {
     const size_t rows = (size_t)g.G * (size_t)g.N;
     dim3 grid((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64))), block(kThreads);
     if (dtype == LASP2_F32)
         hipLaunchKernelGGL(softmax_delta_kernel<float>, grid, block, 0, st, g, static_cast<const float*>(O),
-                           static_cast<const float*>(dO), delta);
+                           static_cast<const float*>(dO), LSE, delta, lse2);
     else
         hipLaunchKernelGGL(softmax_delta_kernel<__hip_bfloat16>, grid, block, 0, st, g,
-                           static_cast<const __hip_bfloat16*>(O), static_cast<const __hip_bfloat16*>(dO), delta);
+                           static_cast<const __hip_bfloat16*>(O), static_cast<const __hip_bfloat16*>(dO), LSE,
+                           delta, lse2);
     return hipGetLastError();
 }
 

@@ -1180,6 +1180,11 @@ __device__ __forceinline__ float xor32(float x)
     return __shfl_xor(x, 32, 64);
 }
 
+// 2^x by the hardware instruction alone: arguments here are <= 0 up to rounding (scores minus a
+// maximum or a log-sum-exp), results below the smallest normal number may flush to zero, and
+// -inf gives 0.  (exp2f adds range scaling for denormal results: four more instructions per call.)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ int wave_min_i(int x)
 {
 #pragma unroll
@@ -1252,8 +1257,10 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     }
     // bounds over the wave's valid queries, for the per-tile decision
     const bool valid = qi < g.N;
-    const int lo_min = wave_min_i(valid ? lo_i : g.N), lo_max = wave_max_i(valid ? lo_i : 0);
-    const int hi_min = wave_min_i(valid ? hi_i : g.N), hi_max = wave_max_i(valid ? hi_i : 0);
+    const int lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? lo_i : g.N));
+    const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_i : 0));
+    const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_i : g.N));
+    const int hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? hi_i : 0));
 
     const int kb0 = blo / KB, kb1 = (bhi + KB - 1) / KB;   // key blocks [kb0, kb1)
     const int NBK = kb1 - kb0;
@@ -1351,11 +1358,11 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
             mx = fmaxf(mx, xor32(mx));
             const float m_new = fmaxf(m, mx * scale_log2e);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // nothing seen yet: all terms are 0
-            const float alpha = exp2f(m - m_use);
+            const float alpha = fast_exp2(m - m_use);
             float ps = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                sc[v] = exp2f(fmaf(sc[v], scale_log2e, -m_use));
+                sc[v] = fast_exp2(fmaf(sc[v], scale_log2e, -m_use));
                 ps += sc[v];
             }
             lsum = fmaf(lsum, alpha, ps);
@@ -1554,13 +1561,19 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) dp = mfma(bufB[ks], gf[ks + 4], dp);
             SCHED_FENCE();
-            // dS = P (dP - delta) / sqrt(d), P = exp2(scale_log2e s - lse2); zero outside the mask
+            // P (dP - delta), P = exp2(scale_log2e s - lse2), zero outside the mask (the factor
+            // 1/sqrt(d) of dS is applied once, to the finished sum)
+            if (whole) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = k0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                const bool keep = whole || (key >= lo_i && key < hi_i);
-                const float p = exp2f(fmaf(sc[v], scale_log2e, -lse2));
-                sc[v] = keep ? p * (dp[v] - dlt) * scale : 0.f;
+                for (int v = 0; v < 16; ++v)
+                    sc[v] = fast_exp2(fmaf(sc[v], scale_log2e, -lse2)) * (dp[v] - dlt);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    const float arg = (key >= lo_i && key < hi_i) ? fmaf(sc[v], scale_log2e, -lse2) : -INFINITY;
+                    sc[v] = fast_exp2(arg) * (dp[v] - dlt);
+                }
             }
             SCHED_FENCE();
 #pragma unroll
@@ -1592,7 +1605,8 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const f32x16& o = Oacc[2 * hv + tvv];
-                    u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                    u32x2 pk = {pack2(o[4 * q] * scale, o[4 * q + 1] * scale),
+                                pack2(o[4 * q + 2] * scale, o[4 * q + 3] * scale)};
                     *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
                 }
 #pragma unroll
@@ -1612,7 +1626,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 // =====================================================================================
 // Softmax attention backward, dK and dV: one workgroup of four waves per 128 keys (32 per wave,
 // one per lane), queries and their dO rows streamed in 64-token stages together with each
-// query's log-sum-exp and delta.  With scores laid out queries x keys, every per-key quantity
+// query's log-sum-exp (times log2 e, as the delta kernel leaves it in LSE2) and delta.  With scores laid out queries x keys, every per-key quantity
 // (mask bounds, the K and V rows as B operands, the two accumulators' columns) is per lane:
 //   S = Q_tile K_w^T, dP = dO_tile V_w^T, P = exp(S/sqrt(d) - lse), dS = P (dP - delta)/sqrt(d),
 //   dV^T += dO_tile^T P,  dK^T += Q_tile^T dS.
@@ -1628,7 +1642,7 @@ __device__ __forceinline__ void dma4(const char* sbase, uint32_t voff, uint32_t 
 
 __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     Geom g, const char* __restrict__ Q, const char* __restrict__ K, const char* __restrict__ V,
-    const char* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const char* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ delta,
     char* __restrict__ dK, char* __restrict__ dV, int causal, float scale_log2e, float scale)
 {
     constexpr int NW = SK_NW, DPS = 2 * (16 / NW) + 2;
@@ -1673,12 +1687,12 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     uint32_t dvo[16 / NW];
 #pragma unroll
     for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
-    const char* lse_g = reinterpret_cast<const char*>(LSE + (size_t)grp * g.N);
+    const char* lse_g = reinterpret_cast<const char*>(LSE2 + (size_t)grp * g.N);
     const char* dlt_g = reinterpret_cast<const char*>(delta + (size_t)grp * g.N);
     auto issue = [&](int i) {
         const int st = i % NSTAGE, q0 = (qb0 + i) * KB;
         dma_block<NW>(Q, dO, base, q0, g.N, sQ + st * STAGE_BYTES, sG + st * STAGE_BYTES, w, lane, dvo);
-        // every wave fetches the stage's 64 lse and 64 delta values (the same bytes to the same
+        // every wave fetches the stage's 64 log2-domain lse and 64 delta values (the same bytes to the same
         // place), which keeps the number of loads in flight equal across waves
         const uint32_t vo = 4u * (uint32_t)min(q0 + lane, g.N - 1);
         dma4(lse_g, vo, lds_addr_of(sL + st * 512));
@@ -1772,14 +1786,23 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
                 bufG[4 + tv] = lds_read_tr8_at(tGh + 16 * ROWB, PV0(tv), PV1(tv));
             }
             SCHED_FENCE();
-            // P and dS in place of the scores and dP; zero outside the mask
+            // P and P (dP - delta) in place of the scores and dP, zero outside the mask; the staged
+            // log-sum-exp is already in the base-2 domain, and the factor 1/sqrt(d) of dS is
+            // applied once, to the finished dK
+            if (whole) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int qi = q0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                const bool keep = whole || (qi >= lo_j && qi < hi_j);
-                const float pr = exp2f(fmaf(sc[v], scale_log2e, -1.4426950408889634f * ls[v >> 2][v & 3]));
-                sc[v] = keep ? pr : 0.f;
-                dp[v] = keep ? pr * (dp[v] - dl[v >> 2][v & 3]) * scale : 0.f;
+                for (int v = 0; v < 16; ++v) {
+                    sc[v] = fast_exp2(fmaf(sc[v], scale_log2e, -ls[v >> 2][v & 3]));
+                    dp[v] = sc[v] * (dp[v] - dl[v >> 2][v & 3]);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int qi = q0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    const float arg = (qi >= lo_j && qi < hi_j) ? fmaf(sc[v], scale_log2e, -ls[v >> 2][v & 3]) : -INFINITY;
+                    sc[v] = fast_exp2(arg);
+                    dp[v] = sc[v] * (dp[v] - dl[v >> 2][v & 3]);
+                }
             }
             {
                 u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
@@ -1821,7 +1844,8 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const f32x16& o = which ? Vacc[2 * hv + tvv] : Kacc[2 * hv + tvv];
-                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                        const float f = which ? 1.f : scale;
+                        u32x2 pk = {pack2(o[4 * q] * f, o[4 * q + 1] * f), pack2(o[4 * q + 2] * f, o[4 * q + 3] * f)};
                         *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
                     }
 #pragma unroll
@@ -1925,7 +1949,7 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
 bool softmax_mfma_supported(const Geom& g, int dtype) { return dtype == LASP2_BF16 && g.d == D; }
 
 hipError_t launch_softmax_bwd_dkv_mfma(const Geom& g, const void* Q, const void* K, const void* V,
-                                       const void* dO, const float* LSE, const float* delta, void* dK,
+                                       const void* dO, const float* LSE2, const float* delta, void* dK,
                                        void* dV, int causal, hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + NSTAGE * 512;   // 97.5 KiB
@@ -1938,7 +1962,7 @@ hipError_t launch_softmax_bwd_dkv_mfma(const Geom& g, const void* Q, const void*
     const float scale = 1.f / sqrtf((float)g.d);
     hipLaunchKernelGGL(softmax_bwd_dkv_mfma_kernel, dim3(gx), dim3(SK_NW * 64), smem, st, g,
                        static_cast<const char*>(Q), static_cast<const char*>(K),
-                       static_cast<const char*>(V), static_cast<const char*>(dO), LSE, delta,
+                       static_cast<const char*>(V), static_cast<const char*>(dO), LSE2, delta,
                        static_cast<char*>(dK), static_cast<char*>(dV), causal,
                        1.4426950408889634f * scale, scale);
     return hipGetLastError();

@@ -297,7 +297,7 @@ int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
     bool empty = false;
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
-    *bytes = (size_t)g.G * (size_t)g.N * sizeof(float);
+    *bytes = 2 * (size_t)g.G * (size_t)g.N * sizeof(float);   // delta, and the log-sum-exp in base 2
     return LASP2_OK;
 }
 
@@ -313,15 +313,18 @@ int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, co
     if (empty) return LASP2_OK;
     rc = check_ptrs({Q, K, V, O, dO, LSE, dQ, dK, dV, workspace});
     if (rc != LASP2_OK) return rc;
-    if (workspace_bytes < (size_t)g.G * (size_t)g.N * sizeof(float)) return LASP2_ERR_WORKSPACE;
+    const size_t rows = (size_t)g.G * (size_t)g.N;
+    if (workspace_bytes < 2 * rows * sizeof(float)) return LASP2_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     float* delta = static_cast<float*>(workspace);
-    hipError_t e = launch_softmax_delta(g, desc->dtype, O, dO, delta, st);
+    float* lse2 = delta + rows;
+    const bool fast = softmax_mfma_supported(g, desc->dtype);
+    hipError_t e = launch_softmax_delta(g, desc->dtype, O, dO, LSE, delta, fast ? lse2 : nullptr, st);
     if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    if (softmax_mfma_supported(g, desc->dtype)) {
+    if (fast) {
         e = launch_softmax_bwd_dq_mfma(g, Q, K, V, dO, LSE, delta, dQ, causal ? 1 : 0, st);
         if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-        return from_hip(launch_softmax_bwd_dkv_mfma(g, Q, K, V, dO, LSE, delta, dK, dV, causal ? 1 : 0, st));
+        return from_hip(launch_softmax_bwd_dkv_mfma(g, Q, K, V, dO, lse2, delta, dK, dV, causal ? 1 : 0, st));
     }
     return from_hip(launch_softmax_bwd_generic(g, desc->dtype, Q, K, V, dO, LSE, delta, dQ, dK, dV,
                                                causal ? 1 : 0, st));

@@ -110,9 +110,10 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
 // Softmax attention forward over the whole sequence (document) of each group.
 hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
                                       const void* V, void* O, float* LSE, int causal, hipStream_t st);
-// delta[g][i] = dO_i . O_i, then dQ, dK, dV of softmax attention from Q, K, V, dO, LSE, delta.
-hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, float* delta,
-                                hipStream_t st);
+// delta[g][i] = dO_i . O_i (and, if lse2 != NULL, lse2[g][i] = LSE[g][i] * log2 e), then dQ, dK, dV of
+// softmax attention from Q, K, V, dO, LSE, delta.  The matrix-core dK/dV kernel takes lse2.
+hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, const float* LSE,
+                                float* delta, float* lse2, hipStream_t st);
 // (dQ == NULL: only dK, dV are computed; dK == NULL: only dQ)
 hipError_t launch_softmax_bwd_generic(const Geom& g, int dtype, const void* Q, const void* K,
                                       const void* V, const void* dO, const float* LSE, const float* delta,

@@ -176,3 +176,44 @@ def test_cfg3_with_decay(oracle):
             errs[k] = rel_l2(_gpu_group(out[k], g)[rows], ref)
             assert errs[k] <= TOL[dtype], (g, errs)
         print(f"group {g}:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+
+
+SOFTMAX_BENCH = dict(B=1, H=16, N=32768, d=128, dtype="bf16", seed=41)
+
+
+def test_softmax_attention_bench_configuration(oracle):
+    """Softmax attention at the size bench.py --softmax times (N=32768, causal): one head's whole
+    output and log-sum-exp against the definition, and sampled rows of dQ, dK, dV against the
+    definition evaluated row by row from that head's fp64 forward."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    c = SOFTMAX_BENCH
+    B, H, N, d, dtype, seed = (c[k] for k in ("B", "H", "N", "d", "dtype", "seed"))
+    p = bd.Problem(B, H, N, d, 64, 0, dtype)
+    dev = {}
+    for n in ("Q", "K", "V", "dO"):
+        host = synth.gen_tensor(seed, n, B * H, N, d, dtype, workers=16) * np.float32(np.sqrt(d) if n != "dO" else 1.0)
+        dev[n] = torch.from_numpy(host).reshape(B, H, N, d).to("cuda").to(p.torch_dtype)
+        del host
+    O = torch.empty_like(dev["Q"])
+    LSE = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_fwd(p, dev["Q"], dev["K"], dev["V"], O, LSE, True)
+    dQ, dK, dV = (torch.empty_like(O) for _ in range(3))
+    ws = torch.empty(bd.lasp2_softmax_workspace_size(p), dtype=torch.uint8, device="cuda")
+    bd.lasp2_softmax_bwd(p, dev["Q"], dev["K"], dev["V"], O, dev["dO"], LSE, dQ, dK, dV, ws, True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(41)
+    g = 6
+    x = {n: _gpu_group(dev[n], g) for n in ("Q", "K", "V", "dO")}   # the bf16 values the kernels read
+    O_ref, lse_ref = oracle.softmax_fwd(x["Q"][None], x["K"][None], x["V"][None], True)
+    errs = {"O": rel_l2(_gpu_group(O, g), O_ref[0]),
+            "LSE": float(np.max(np.abs(LSE.reshape(B * H, N)[g].cpu().numpy() - lse_ref[0])))}
+    assert errs["O"] <= TOL[dtype] and errs["LSE"] <= 2e-3, errs
+    delta = np.sum(x["dO"] * O_ref[0], axis=1)
+    rows = np.unique(np.concatenate([rng.integers(0, N, 40), [0, 1, 127, 128, 255, 256, N - 129, N - 1]])).astype(np.int64)
+    for which, t in enumerate((dQ, dK, dV)):
+        ref = oracle.softmax_bwd_rows(x["Q"], x["K"], x["V"], x["dO"], lse_ref[0], delta, rows, which, True)
+        k = ("dQ", "dK", "dV")[which]
+        errs[k] = rel_l2(_gpu_group(t, g)[rows], ref)
+        assert errs[k] <= TOL[dtype], errs
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
