@@ -14,6 +14,7 @@
 // LDS tiles have 256-byte rows (128 bf16) with their 16-byte chunks XOR-swizzled by
 // swz(row), which keeps both access shapes free of bank conflicts without padding.
 #include "lasp2_common.h"
+#include <type_traits>
 
 namespace lasp2 {
 namespace {
@@ -69,6 +70,27 @@ __device__ __forceinline__ bf16x8 lds_read16_at(const char* base, int lane_off)
 {
     return *reinterpret_cast<const bf16x8*>(base + lane_off);
 }
+
+// The same two reads from 32-bit LDS addresses (a per-lane register that already contains the
+// array's base, plus a compile-time constant): the constant goes into the instruction's offset
+// field, so the read costs no address arithmetic.
+__device__ __forceinline__ bf16x8 lds_read16_u(uint32_t addr)
+{
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(addr);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr8_u(uint32_t addr_lo, uint32_t addr_hi)
+{
+    typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(addr_lo));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4_ptr>(addr_hi));
+    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// Makes a computed per-lane value opaque to the compiler, so that it is kept in its register
+// instead of being re-derived from its parts (one more add) at every use inside a loop.
+__device__ __forceinline__ void pin_vgpr(uint32_t& x) { asm volatile("" : "+v"(x)); }
 
 __device__ __forceinline__ bf16x8 lds_read_tr8_at(const char* base, int off_lo, int off_hi)
 {
@@ -1274,17 +1296,24 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     issue(0);
     if (NBK > 1) issue(1);
 
-    int nat[8], pv[4][2];
+    // per-lane LDS addresses of the natural reads (K stages) and the transposed reads (V stages)
+    // inside ring slot 0, first half; slot and half are added as immediates at the point of use
+    uint32_t nat[8], pv[4][2];
     {
         const int i = lane & 15, g2 = (lane >> 4) & 1;
         const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
+        const uint32_t aK = lds_addr_of(sK), aV = lds_addr_of(sV);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) nat[ks] = tile_off(l32, 2 * ks + h);
+        for (int ks = 0; ks < 8; ++ks) nat[ks] = aK + tile_off(l32, 2 * ks + h);
 #pragma unroll
         for (int tv = 0; tv < 4; ++tv) {
-            pv[tv][0] = tr_off(4 * h + rl, 32 * tv + cl);
-            pv[tv][1] = tr_off(8 + 4 * h + rl, 32 * tv + cl);
+            pv[tv][0] = aV + tr_off(4 * h + rl, 32 * tv + cl);
+            pv[tv][1] = aV + tr_off(8 + 4 * h + rl, 32 * tv + cl);
         }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) pin_vgpr(nat[ks]);
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) { pin_vgpr(pv[tv][0]); pin_vgpr(pv[tv][1]); }
     }
 
     // this wave's 32 queries as B-operand fragments (column = query, k = d); zero past the end
@@ -1307,9 +1336,13 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     float m = -INFINITY;   // running maximum of scale_log2e * score (shared by lanes l, l+32)
     float lsum = 0.f;      // this lane's part of the running sum of exp2(. - m)
 
-    for (int bi = 0; bi < NBK; ++bi) {
-        char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
-        char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+    // One key block.  The ring slot is a compile-time constant (the block loop below is unrolled
+    // by the ring length), which turns every LDS address into a per-lane register plus an
+    // immediate offset: no address arithmetic in the loop.
+    auto block = [&](auto stage_c, int bi) {
+        constexpr int ST = decltype(stage_c)::value;
+        char* tK = sK + ST * STAGE_BYTES;
+        char* tV = sV + ST * STAGE_BYTES;
         const int k0b = (kb0 + bi) * KB;
         if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
         if (k0b + KB > g.N) zero_tail_rows<NW>(k0b, g.N, tK, tV, w, lane);
@@ -1323,9 +1356,9 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
             if (k0 >= hi_max || k0 + 32 <= lo_min) continue;   // no query of this wave sees it
             const bool whole = (k0 >= lo_max) && (k0 + 32 <= hi_min);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), nat[ks]);
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_u(nat[ks] + (ST * STAGE_BYTES + half * (32 * ROWB)));
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tK + half * (32 * ROWB), nat[ks + 4]);
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_u(nat[ks + 4] + (ST * STAGE_BYTES + half * (32 * ROWB)));
             SCHED_FENCE();
             f32x16 sc;
 #pragma unroll
@@ -1335,14 +1368,16 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
             SCHED_FENCE();
 #pragma unroll
             for (int tv = 0; tv < 4; ++tv)
-                bufA[tv] = lds_read_tr8_at(tV + half * (32 * ROWB), pv[tv][0], pv[tv][1]);
+                bufA[tv] = lds_read_tr8_u(pv[tv][0] + (ST * STAGE_BYTES + half * (32 * ROWB)),
+                                          pv[tv][1] + (ST * STAGE_BYTES + half * (32 * ROWB)));
             SCHED_FENCE();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
             SCHED_FENCE();
 #pragma unroll
             for (int tv = 0; tv < 4; ++tv)
-                bufB[tv] = lds_read_tr8_at(tV + half * (32 * ROWB) + 16 * ROWB, pv[tv][0], pv[tv][1]);
+                bufB[tv] = lds_read_tr8_u(pv[tv][0] + (ST * STAGE_BYTES + half * (32 * ROWB) + 16 * ROWB),
+                                          pv[tv][1] + (ST * STAGE_BYTES + half * (32 * ROWB) + 16 * ROWB));
             SCHED_FENCE();
             if (!whole) {
 #pragma unroll
@@ -1387,6 +1422,12 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
             }
             SCHED_FENCE();
         }
+    };
+    static_assert(NSTAGE == 3, "the block loop is unrolled by the ring length");
+    for (int bi = 0; bi < NBK; bi += 3) {
+        block(std::integral_constant<int, 0>{}, bi);
+        if (bi + 1 < NBK) block(std::integral_constant<int, 1>{}, bi + 1);
+        if (bi + 2 < NBK) block(std::integral_constant<int, 2>{}, bi + 2);
     }
 
     // normalise, write the log-sum-exp, store through the wave's LDS patch
@@ -1677,10 +1718,8 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
         doc_range(g, kj, lo_j, hi_j);
         if (causal) lo_j = kj;
     }
-    const int lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? lo_j : g.N));
-    const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_j : 0));
-    const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_j : g.N));
-    const int hi_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? hi_j : 0));
+    const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_j : g.N));
+    const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_j : 0));
 
     const int qb0 = blo / KB, qb1 = (bhi + KB - 1) / KB;
     const int NBK = qb1 - qb0;
@@ -1701,17 +1740,32 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     issue(0);
     if (NBK > 1) issue(1);
 
-    const int nat0 = tile_off(l32, h);
-    int pv0, pv1;
+    // per-lane LDS addresses inside ring slot 0, first half: natural reads of Q and dO tiles
+    // (row = query), transposed reads of both (row = d), and the lane's quarter of the staged
+    // log-sum-exp / delta values; slot, half and k-step are added as immediates at the use
+    uint32_t natQ[8], natG[8], trQ[4][2], trG[4][2], aL;
     {
         const int i = lane & 15, g2 = (lane >> 4) & 1;
         const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
-        pv0 = tr_off(4 * h + rl, cl);
-        pv1 = tr_off(8 + 4 * h + rl, cl);
+        const uint32_t aQ = lds_addr_of(sQ), aG = lds_addr_of(sG);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            natQ[ks] = aQ + tile_off(l32, 2 * ks + h);
+            natG[ks] = aG + tile_off(l32, 2 * ks + h);
+            pin_vgpr(natQ[ks]);
+            pin_vgpr(natG[ks]);
+        }
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) {
+            trQ[tv][0] = aQ + tr_off(4 * h + rl, 32 * tv + cl);
+            trQ[tv][1] = aQ + tr_off(8 + 4 * h + rl, 32 * tv + cl);
+            trG[tv][0] = aG + tr_off(4 * h + rl, 32 * tv + cl);
+            trG[tv][1] = aG + tr_off(8 + 4 * h + rl, 32 * tv + cl);
+            pin_vgpr(trQ[tv][0]); pin_vgpr(trQ[tv][1]); pin_vgpr(trG[tv][0]); pin_vgpr(trG[tv][1]);
+        }
+        aL = lds_addr_of(sL) + 16 * h;
+        pin_vgpr(aL);
     }
-#define NAT(ks) (nat0 ^ ((ks) << 5))
-#define PV0(tv) (pv0 ^ ((tv) << 6))
-#define PV1(tv) (pv1 ^ ((tv) << 6))
 
     // this wave's 32 keys: K and V rows as B-operand fragments; zero past the end
     bf16x8 kf[8], vf[8];
@@ -1733,99 +1787,142 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) { Kacc[tv][v] = 0.f; Vacc[tv][v] = 0.f; }
 
-    for (int bi = 0; bi < NBK; ++bi) {
-        const int st = bi % NSTAGE;
-        char* tQ = sQ + st * STAGE_BYTES;
-        char* tG = sG + st * STAGE_BYTES;
-        const char* tL = sL + st * 512;
+    typedef const __attribute__((address_space(3))) f32x4* lds_f32x4_ptr;
+
+    // One stage of 64 queries.  The ring slot is a compile-time constant (the loop below is
+    // unrolled by the ring length), so every LDS read is a pinned register plus an immediate.
+    auto block = [&](auto stage_c, int bi) {
+        constexpr int ST = decltype(stage_c)::value;
+        constexpr uint32_t SO = ST * STAGE_BYTES;
         const int q0b = (qb0 + bi) * KB;
         if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
-        if (q0b + KB > g.N) zero_tail_rows<NW>(q0b, g.N, tQ, tG, w, lane);
+        if (q0b + KB > g.N) zero_tail_rows<NW>(q0b, g.N, sQ + SO, sG + SO, w, lane);
         __syncthreads();
         if (bi + 2 < NBK) issue(bi + 2);
 
+        // The mask enters through the accumulators the score products start from: 0 where the
+        // (query, key) pair is kept, -inf where it is not, so that P = exp2(-inf) = 0 and
+        // dS = 0 * (dP - delta) = 0 there with no compare in the per-element code.  Halves inside
+        // every lane's range (all but the few at mask edges) start from zeros.  One code path for
+        // every block also keeps the two accumulators in place from block to block.
+        // The two halves are software-pipelined so that one half's exponentials run under the
+        // other's MFMAs (a workgroup has one wave per SIMD; nothing else would fill those slots).
+        const bool whole0 = (q0b >= lo_max) && (q0b + 32 <= hi_min);
+        const bool whole1 = (q0b + 32 >= lo_max) && (q0b + 64 <= hi_min);
+        bf16x8 A0[8], B0[8], A1[8], B1[8];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int q0 = q0b + 32 * half;
-            if (q0 >= hi_max || q0 + 32 <= lo_min) continue;
-            const bool whole = (q0 >= lo_max) && (q0 + 32 <= hi_min);
-            const char* tQh = tQ + half * (32 * ROWB);
-            const char* tGh = tG + half * (32 * ROWB);
-            bf16x8 bufQ[8], bufG[8];
+        for (int ks = 0; ks < 8; ++ks) A0[ks] = lds_read16_u(natQ[ks] + SO);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) bufQ[ks] = lds_read16_at(tQh, NAT(ks));
+        for (int ks = 0; ks < 8; ++ks) B0[ks] = lds_read16_u(natG[ks] + SO);
+        f32x4 ls[4], dl[4];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) bufG[ks] = lds_read16_at(tGh, NAT(ks));
-            // the queries of this lane's 16 result rows: 8 (v/4) + 4 h + v%4
-            f32x4 ls[4], dl[4];
+        for (int q = 0; q < 4; ++q) {
+            ls[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 32 * q));
+            dl[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 256 + 32 * q));
+        }
+        SCHED_FENCE();
+        // phase A: S0 = Q0 K^T, dP0 = dO0 V^T
+        f32x16 sc0, dp0, sc1, dp1;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                ls[q] = *reinterpret_cast<const f32x4*>(tL + (32 * half + 8 * q + 4 * h) * 4);
-                dl[q] = *reinterpret_cast<const f32x4*>(tL + 256 + (32 * half + 8 * q + 4 * h) * 4);
+        for (int v = 0; v < 16; ++v) { sc0[v] = 0.f; dp0[v] = 0.f; sc1[v] = 0.f; dp1[v] = 0.f; }
+        if (!whole0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0b + 8 * (v >> 2) + 4 * h + (v & 3);
+                sc0[v] = (qi >= lo_j && qi < hi_j) ? 0.f : -INFINITY;
             }
-            SCHED_FENCE();
-            f32x16 sc, dp;
+        }
+        if (!whole1) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) sc = mfma(bufQ[ks], kf[ks], sc);
-            SCHED_FENCE();
-            // transposed operands of the two accumulations, fetched under the dP products
-#pragma unroll
-            for (int tv = 0; tv < 4; ++tv) {
-                bufQ[tv] = lds_read_tr8_at(tQh, PV0(tv), PV1(tv));
-                bufQ[4 + tv] = lds_read_tr8_at(tQh + 16 * ROWB, PV0(tv), PV1(tv));
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0b + 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                sc1[v] = (qi >= lo_j && qi < hi_j) ? 0.f : -INFINITY;
             }
-            SCHED_FENCE();
+        }
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) dp = mfma(bufG[ks], vf[ks], dp);
-            SCHED_FENCE();
+        for (int ks = 0; ks < 8; ++ks) {
+            sc0 = mfma(A0[ks], kf[ks], sc0);
+            dp0 = mfma(B0[ks], vf[ks], dp0);
+        }
+        SCHED_FENCE();
+        // transposed operands of half 0 (into the registers its natural operands used)
 #pragma unroll
-            for (int tv = 0; tv < 4; ++tv) {
-                bufG[tv] = lds_read_tr8_at(tGh, PV0(tv), PV1(tv));
-                bufG[4 + tv] = lds_read_tr8_at(tGh + 16 * ROWB, PV0(tv), PV1(tv));
+        for (int tv = 0; tv < 4; ++tv) {
+            A0[tv] = lds_read_tr8_u(trQ[tv][0] + SO, trQ[tv][1] + SO);
+            A0[4 + tv] = lds_read_tr8_u(trQ[tv][0] + (SO + 16 * ROWB), trQ[tv][1] + (SO + 16 * ROWB));
+            B0[tv] = lds_read_tr8_u(trG[tv][0] + SO, trG[tv][1] + SO);
+            B0[4 + tv] = lds_read_tr8_u(trG[tv][0] + (SO + 16 * ROWB), trG[tv][1] + (SO + 16 * ROWB));
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            A1[ks] = lds_read16_u(natQ[ks] + (SO + 32 * ROWB));
+            B1[ks] = lds_read16_u(natG[ks] + (SO + 32 * ROWB));
+        }
+        SCHED_FENCE();
+        // phase B: S1, dP1 on the matrix unit (operands fetched two steps ahead, which keeps few
+        // of them alive at a time); P0 and P0 (dP0 - delta) on the vector unit
+        uint32_t pp0[8], pd0[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j + 2 < 8) {
+                A1[j + 2] = lds_read16_u(natQ[j + 2] + (SO + 32 * ROWB));
+                B1[j + 2] = lds_read16_u(natG[j + 2] + (SO + 32 * ROWB));
             }
-            SCHED_FENCE();
-            // P and P (dP - delta) in place of the scores and dP, zero outside the mask; the staged
-            // log-sum-exp is already in the base-2 domain, and the factor 1/sqrt(d) of dS is
-            // applied once, to the finished dK
-            if (whole) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    sc[v] = fast_exp2(fmaf(sc[v], scale_log2e, -ls[v >> 2][v & 3]));
-                    dp[v] = sc[v] * (dp[v] - dl[v >> 2][v & 3]);
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int qi = q0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                    const float arg = (qi >= lo_j && qi < hi_j) ? fmaf(sc[v], scale_log2e, -ls[v >> 2][v & 3]) : -INFINITY;
-                    sc[v] = fast_exp2(arg);
-                    dp[v] = sc[v] * (dp[v] - dl[v >> 2][v & 3]);
-                }
-            }
-            {
-                u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
-                u32x4 dk = {pack2(dp[0], dp[1]), pack2(dp[2], dp[3]), pack2(dp[4], dp[5]), pack2(dp[6], dp[7])};
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk), db = __builtin_bit_cast(bf16x8, dk);
-#pragma unroll
-                for (int tv = 0; tv < 4; ++tv) {
-                    Vacc[tv] = mfma(bufG[tv], pb, Vacc[tv]);
-                    Kacc[tv] = mfma(bufQ[tv], db, Kacc[tv]);
-                }
-            }
-            {
-                u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
-                u32x4 dk = {pack2(dp[8], dp[9]), pack2(dp[10], dp[11]), pack2(dp[12], dp[13]), pack2(dp[14], dp[15])};
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk), db = __builtin_bit_cast(bf16x8, dk);
-#pragma unroll
-                for (int tv = 0; tv < 4; ++tv) {
-                    Vacc[tv] = mfma(bufG[4 + tv], pb, Vacc[tv]);
-                    Kacc[tv] = mfma(bufQ[4 + tv], db, Kacc[tv]);
-                }
-            }
+            sc1 = mfma(A1[j], kf[j], sc1);
+            dp1 = mfma(B1[j], vf[j], dp1);
+            const int v = 2 * j;
+            const float pa = fast_exp2(fmaf(sc0[v], scale_log2e, -ls[v >> 2][v & 3]));
+            const float pb = fast_exp2(fmaf(sc0[v + 1], scale_log2e, -ls[v >> 2][(v & 3) + 1]));
+            pp0[j] = pack2(pa, pb);
+            pd0[j] = pack2(pa * (dp0[v] - dl[v >> 2][v & 3]), pb * (dp0[v + 1] - dl[v >> 2][(v & 3) + 1]));
             SCHED_FENCE();
         }
+        // half 1's log-sum-exp and delta, and its transposed operands
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            ls[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 128 + 32 * q));
+            dl[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 256 + 128 + 32 * q));
+        }
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) {
+            A1[tv] = lds_read_tr8_u(trQ[tv][0] + (SO + 32 * ROWB), trQ[tv][1] + (SO + 32 * ROWB));
+            A1[4 + tv] = lds_read_tr8_u(trQ[tv][0] + (SO + 48 * ROWB), trQ[tv][1] + (SO + 48 * ROWB));
+            B1[tv] = lds_read_tr8_u(trG[tv][0] + (SO + 32 * ROWB), trG[tv][1] + (SO + 32 * ROWB));
+            B1[4 + tv] = lds_read_tr8_u(trG[tv][0] + (SO + 48 * ROWB), trG[tv][1] + (SO + 48 * ROWB));
+        }
+        SCHED_FENCE();
+        // phase C: half 0 into dV^T, dK^T on the matrix unit; P1 and dS1 on the vector unit
+        uint32_t pp1[8], pd1[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int kst = j >> 2, tv = j & 3;
+            const u32x4 pk = {pp0[4 * kst], pp0[4 * kst + 1], pp0[4 * kst + 2], pp0[4 * kst + 3]};
+            const u32x4 dk = {pd0[4 * kst], pd0[4 * kst + 1], pd0[4 * kst + 2], pd0[4 * kst + 3]};
+            Vacc[tv] = mfma(B0[4 * kst + tv], __builtin_bit_cast(bf16x8, pk), Vacc[tv]);
+            Kacc[tv] = mfma(A0[4 * kst + tv], __builtin_bit_cast(bf16x8, dk), Kacc[tv]);
+            const int v = 2 * j;
+            const float pa = fast_exp2(fmaf(sc1[v], scale_log2e, -ls[v >> 2][v & 3]));
+            const float pb = fast_exp2(fmaf(sc1[v + 1], scale_log2e, -ls[v >> 2][(v & 3) + 1]));
+            pp1[j] = pack2(pa, pb);
+            pd1[j] = pack2(pa * (dp1[v] - dl[v >> 2][v & 3]), pb * (dp1[v + 1] - dl[v >> 2][(v & 3) + 1]));
+            SCHED_FENCE();
+        }
+        // phase D: half 1 into dV^T, dK^T
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int kst = j >> 2, tv = j & 3;
+            const u32x4 pk = {pp1[4 * kst], pp1[4 * kst + 1], pp1[4 * kst + 2], pp1[4 * kst + 3]};
+            const u32x4 dk = {pd1[4 * kst], pd1[4 * kst + 1], pd1[4 * kst + 2], pd1[4 * kst + 3]};
+            Vacc[tv] = mfma(B1[4 * kst + tv], __builtin_bit_cast(bf16x8, pk), Vacc[tv]);
+            Kacc[tv] = mfma(A1[4 * kst + tv], __builtin_bit_cast(bf16x8, dk), Kacc[tv]);
+        }
+        SCHED_FENCE();
+    };
+    static_assert(NSTAGE == 3, "the block loop is unrolled by the ring length");
+    for (int bi = 0; bi < NBK; bi += 3) {
+        block(std::integral_constant<int, 0>{}, bi);
+        if (bi + 1 < NBK) block(std::integral_constant<int, 1>{}, bi + 1);
+        if (bi + 2 < NBK) block(std::integral_constant<int, 2>{}, bi + 2);
     }
 
     // dK^T and dV^T (d x keys) -> rows of dK, dV through a 4 KiB per-wave staging area that
@@ -1858,9 +1955,6 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
             }
         }
     }
-#undef NAT
-#undef PV0
-#undef PV1
 }
 
 }  // namespace
