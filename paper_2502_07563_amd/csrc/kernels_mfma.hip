@@ -1822,9 +1822,9 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
         }
         SCHED_FENCE();
         // phase A: S0 = Q0 K^T, dP0 = dO0 V^T
-        f32x16 sc0, dp0, sc1, dp1;
+        f32x16 sc0, dp0;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sc0[v] = 0.f; dp0[v] = 0.f; sc1[v] = 0.f; dp1[v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { sc0[v] = 0.f; dp0[v] = 0.f; }
         if (!whole0) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -1832,19 +1832,18 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
                 sc0[v] = (qi >= lo_j && qi < hi_j) ? 0.f : -INFINITY;
             }
         }
-        if (!whole1) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int qi = q0b + 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                sc1[v] = (qi >= lo_j && qi < hi_j) ? 0.f : -INFINITY;
-            }
-        }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
+            // the first of half 1's natural operands arrive under these products, into the
+            // registers that half 0's first ones have left
+            if (ks >= 4) {
+                A1[ks - 4] = lds_read16_u(natQ[ks - 4] + (SO + 32 * ROWB));
+                B1[ks - 4] = lds_read16_u(natG[ks - 4] + (SO + 32 * ROWB));
+            }
             sc0 = mfma(A0[ks], kf[ks], sc0);
             dp0 = mfma(B0[ks], vf[ks], dp0);
+            SCHED_FENCE();
         }
-        SCHED_FENCE();
         // transposed operands of half 0 (into the registers its natural operands used)
 #pragma unroll
         for (int tv = 0; tv < 4; ++tv) {
@@ -1853,20 +1852,26 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
             B0[tv] = lds_read_tr8_u(trG[tv][0] + SO, trG[tv][1] + SO);
             B0[4 + tv] = lds_read_tr8_u(trG[tv][0] + (SO + 16 * ROWB), trG[tv][1] + (SO + 16 * ROWB));
         }
+        f32x16 sc1, dp1;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            A1[ks] = lds_read16_u(natQ[ks] + (SO + 32 * ROWB));
-            B1[ks] = lds_read16_u(natG[ks] + (SO + 32 * ROWB));
+        for (int v = 0; v < 16; ++v) { sc1[v] = 0.f; dp1[v] = 0.f; }
+        if (!whole1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = q0b + 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                sc1[v] = (qi >= lo_j && qi < hi_j) ? 0.f : -INFINITY;
+            }
         }
         SCHED_FENCE();
-        // phase B: S1, dP1 on the matrix unit (operands fetched two steps ahead, which keeps few
-        // of them alive at a time); P0 and P0 (dP0 - delta) on the vector unit
+        // phase B: S1, dP1 on the matrix unit; P0 and P0 (dP0 - delta) on the vector unit; half 1's
+        // log-sum-exp and delta replace half 0's as those are used up
         uint32_t pp0[8], pd0[8];
+        f32x4 ls1[4], dl1[4];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (j + 2 < 8) {
-                A1[j + 2] = lds_read16_u(natQ[j + 2] + (SO + 32 * ROWB));
-                B1[j + 2] = lds_read16_u(natG[j + 2] + (SO + 32 * ROWB));
+            if (j < 4) {
+                A1[j + 4] = lds_read16_u(natQ[j + 4] + (SO + 32 * ROWB));
+                B1[j + 4] = lds_read16_u(natG[j + 4] + (SO + 32 * ROWB));
             }
             sc1 = mfma(A1[j], kf[j], sc1);
             dp1 = mfma(B1[j], vf[j], dp1);
@@ -1875,14 +1880,13 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
             const float pb = fast_exp2(fmaf(sc0[v + 1], scale_log2e, -ls[v >> 2][(v & 3) + 1]));
             pp0[j] = pack2(pa, pb);
             pd0[j] = pack2(pa * (dp0[v] - dl[v >> 2][v & 3]), pb * (dp0[v + 1] - dl[v >> 2][(v & 3) + 1]));
+            if (j & 1) {
+                ls1[j >> 1] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 128 + 32 * (j >> 1)));
+                dl1[j >> 1] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 256 + 128 + 32 * (j >> 1)));
+            }
             SCHED_FENCE();
         }
-        // half 1's log-sum-exp and delta, and its transposed operands
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            ls[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 128 + 32 * q));
-            dl[q] = *reinterpret_cast<lds_f32x4_ptr>(aL + (ST * 512 + 256 + 128 + 32 * q));
-        }
+        // half 1's transposed operands
 #pragma unroll
         for (int tv = 0; tv < 4; ++tv) {
             A1[tv] = lds_read_tr8_u(trQ[tv][0] + (SO + 32 * ROWB), trQ[tv][1] + (SO + 32 * ROWB));
@@ -1901,10 +1905,10 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
             Vacc[tv] = mfma(B0[4 * kst + tv], __builtin_bit_cast(bf16x8, pk), Vacc[tv]);
             Kacc[tv] = mfma(A0[4 * kst + tv], __builtin_bit_cast(bf16x8, dk), Kacc[tv]);
             const int v = 2 * j;
-            const float pa = fast_exp2(fmaf(sc1[v], scale_log2e, -ls[v >> 2][v & 3]));
-            const float pb = fast_exp2(fmaf(sc1[v + 1], scale_log2e, -ls[v >> 2][(v & 3) + 1]));
+            const float pa = fast_exp2(fmaf(sc1[v], scale_log2e, -ls1[v >> 2][v & 3]));
+            const float pb = fast_exp2(fmaf(sc1[v + 1], scale_log2e, -ls1[v >> 2][(v & 3) + 1]));
             pp1[j] = pack2(pa, pb);
-            pd1[j] = pack2(pa * (dp1[v] - dl[v >> 2][v & 3]), pb * (dp1[v + 1] - dl[v >> 2][(v & 3) + 1]));
+            pd1[j] = pack2(pa * (dp1[v] - dl1[v >> 2][v & 3]), pb * (dp1[v + 1] - dl1[v >> 2][(v & 3) + 1]));
             SCHED_FENCE();
         }
         // phase D: half 1 into dV^T, dK^T
