@@ -248,6 +248,29 @@ int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                       void* dQ, void* dK, void* dV,
                       void* workspace, size_t workspace_bytes, int causal, void* stream);
 
+/*
+ * One rank's share of the same layer (Algorithm "AllGather-based Context
+ * Parallelism": rank t holds Q_t, gathers K and V, computes O_t): the queries
+ * are the tokens [q_begin, q_begin + q_len) of the N-token sequence.
+ * Q_t, O_t, dO_t, dQ_t are [B,H,q_len,d] and LSE_t is [B,H,q_len], row r being
+ * token q_begin + r (masks use the token index); K, V, dK, dV are [B,H,N,d].
+ * lasp2_softmax_bwd_share writes into dK, dV (all N rows, zeros where no query
+ * of the share attends) this share's contribution only: the terms a
+ * reduce-scatter over ranks would add up.  q_begin < 0, q_len < 0 or
+ * q_begin + q_len > N gives LASP2_ERR_SHAPE; q_len = 0 is allowed.  The
+ * workspace holds two fp32 per query row of the share.  Everything else is as
+ * for lasp2_softmax_fwd / lasp2_softmax_bwd, which are the share
+ * q_begin = 0, q_len = N.
+ */
+int lasp2_softmax_fwd_share(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len,
+                            const void* Q_t, const void* K, const void* V, void* O_t,
+                            float* LSE_t, int causal, void* stream);
+int lasp2_softmax_share_workspace_size(const lasp2_desc_t* desc, int64_t q_len, size_t* bytes);
+int lasp2_softmax_bwd_share(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len,
+                            const void* Q_t, const void* K, const void* V, const void* O_t,
+                            const void* dO_t, const float* LSE_t, void* dQ_t, void* dK, void* dV,
+                            void* workspace, size_t workspace_bytes, int causal, void* stream);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lasp2_status_string(int status);
 

@@ -60,12 +60,17 @@ def lib():
         L.lasp2_softmax_fwd.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_int, vp]
         L.lasp2_softmax_workspace_size.argtypes = [dp, szp]
         L.lasp2_softmax_bwd.argtypes = [dp] + [vp] * 10 + [ctypes.c_size_t, ctypes.c_int, vp]
+        i64 = ctypes.c_int64
+        L.lasp2_softmax_fwd_share.argtypes = [dp, i64, i64, vp, vp, vp, vp, vp, ctypes.c_int, vp]
+        L.lasp2_softmax_share_workspace_size.argtypes = [dp, i64, szp]
+        L.lasp2_softmax_bwd_share.argtypes = [dp, i64, i64] + [vp] * 10 + [ctypes.c_size_t, ctypes.c_int, vp]
         L.lasp2_status_string.argtypes = [ctypes.c_int]
         L.lasp2_status_string.restype = ctypes.c_char_p
         for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
                      "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_state_total",
                      "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd",
-                     "lasp2_softmax_workspace_size", "lasp2_softmax_bwd"):
+                     "lasp2_softmax_workspace_size", "lasp2_softmax_bwd", "lasp2_softmax_fwd_share",
+                     "lasp2_softmax_share_workspace_size", "lasp2_softmax_bwd_share"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -185,6 +190,28 @@ def lasp2_softmax_bwd(p: Problem, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, ca
     _check(lib().lasp2_softmax_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
                                    1 if causal else 0, _stream(stream)), "lasp2_softmax_bwd")
+
+
+def lasp2_softmax_fwd_share(p: Problem, q_begin, q_len, Q_t, K, V, O_t, LSE_t, causal=False, stream=None):
+    _check(lib().lasp2_softmax_fwd_share(p.ref, ctypes.c_int64(q_begin), ctypes.c_int64(q_len), _ptr(Q_t),
+                                         _ptr(K), _ptr(V), _ptr(O_t), _ptr(LSE_t), 1 if causal else 0,
+                                         _stream(stream)), "lasp2_softmax_fwd_share")
+
+
+def lasp2_softmax_share_workspace_size(p: Problem, q_len) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lasp2_softmax_share_workspace_size(p.ref, ctypes.c_int64(q_len), ctypes.byref(out)),
+           "lasp2_softmax_share_workspace_size")
+    return out.value
+
+
+def lasp2_softmax_bwd_share(p: Problem, q_begin, q_len, Q_t, K, V, O_t, dO_t, LSE_t, dQ_t, dK, dV, workspace,
+                            causal=False, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lasp2_softmax_bwd_share(p.ref, ctypes.c_int64(q_begin), ctypes.c_int64(q_len), _ptr(Q_t),
+                                         _ptr(K), _ptr(V), _ptr(O_t), _ptr(dO_t), _ptr(LSE_t), _ptr(dQ_t),
+                                         _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
+                                         1 if causal else 0, _stream(stream)), "lasp2_softmax_bwd_share")
 
 
 def alloc_states(p: Problem, device="cuda"):

@@ -341,14 +341,15 @@ __global__ __launch_bounds__(kThreads) void softmax_fwd_generic_kernel(Geom g, c
     __shared__ float sAlpha[kSmRows], sM[kSmRows], sL[kSmRows];
     __shared__ int sLo[kSmRows], sHi[kSmRows];
     const int tid = threadIdx.x, grp = blockIdx.y;
-    const int r0 = blockIdx.x * kSmRows;
-    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+    const int r0 = blockIdx.x * kSmRows;                    // first of this workgroup's query rows
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;     // K, V
+    const size_t qbase = (size_t)grp * (size_t)g.qn * D;    // Q, O (row r = token q0 + r)
     const float scale = rsqrtf((float)D);
 
     if (tid < kSmRows) {
-        const int i = r0 + tid;
+        const int i = g.q0 + r0 + tid;
         int lo = 0, hi = 0;
-        if (i < g.N) {
+        if (r0 + tid < g.qn) {
             lo = 0; hi = g.N;
             for (int k = 0; k < g.n_seqs; ++k)
                 if (g.cu[k] <= i && i < g.cu[k + 1]) { lo = g.cu[k]; hi = g.cu[k + 1]; }
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void softmax_fwd_generic_kernel(Geom g, c
     }
     for (int idx = tid; idx < kSmRows * D; idx += kThreads) {
         const int r = idx / D, a = idx % D;
-        sQ[r][a] = (r0 + r < g.N) ? ld(Q + gbase + (size_t)(r0 + r) * D + a) : 0.f;
+        sQ[r][a] = (r0 + r < g.qn) ? ld(Q + qbase + (size_t)(r0 + r) * D + a) : 0.f;
     }
     __syncthreads();
     int klo = g.N, khi = 0;
@@ -409,11 +410,11 @@ __global__ __launch_bounds__(kThreads) void softmax_fwd_generic_kernel(Geom g, c
         }
         __syncthreads();
     }
-    if (r0 + myr < g.N) {
+    if (r0 + myr < g.qn) {
         const float inv = 1.f / sL[myr];
 #pragma unroll
-        for (int u = 0; u < CPT; ++u) st(O + gbase + (size_t)(r0 + myr) * D + c0 + u * TPR, acc[u] * inv);
-        if (c0 == 0) LSE[(size_t)grp * g.N + r0 + myr] = sM[myr] + logf(sL[myr]);
+        for (int u = 0; u < CPT; ++u) st(O + qbase + (size_t)(r0 + myr) * D + c0 + u * TPR, acc[u] * inv);
+        if (c0 == 0) LSE[(size_t)grp * g.qn + r0 + myr] = sM[myr] + logf(sL[myr]);
     }
 }
 
@@ -421,7 +422,7 @@ template <typename T>
 hipError_t softmax_fwd_generic_T(const Geom& g, const T* Q, const T* K, const T* V, T* O, float* LSE,
                                  int causal, hipStream_t st)
 {
-    dim3 grid((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
+    dim3 grid((g.qn + kSmRows - 1) / kSmRows, g.G), block(kThreads);
     switch (g.d) {
         case 16: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 16>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
         case 32: hipLaunchKernelGGL((softmax_fwd_generic_kernel<T, 32>), grid, block, 0, st, g, Q, K, V, O, LSE, causal); break;
@@ -441,7 +442,7 @@ __global__ __launch_bounds__(kThreads) void softmax_delta_kernel(Geom g, const T
                                                                  float* __restrict__ delta,
                                                                  float* __restrict__ lse2)
 {
-    const size_t rows = (size_t)g.G * (size_t)g.N;
+    const size_t rows = (size_t)g.G * (size_t)g.qn;
     const size_t row = (size_t)blockIdx.x * (kThreads / 64) + threadIdx.x / 64;
     if (row >= rows) return;
     const int lane = threadIdx.x % 64;
@@ -472,33 +473,42 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_generic_kernel(
     __shared__ float sP[kSmRows][kSmKeys + 1], sDS[kSmRows][kSmKeys + 1];
     __shared__ int sLo[kSmRows], sHi[kSmRows];
     const int tid = threadIdx.x, grp = blockIdx.y;
-    const int r0 = blockIdx.x * kSmRows;
-    const size_t gbase = (size_t)grp * (size_t)g.N * D;
+    const int r0 = blockIdx.x * kSmRows;      // own rows: local query rows (dQ) or keys (dK, dV)
+    const size_t gbase = (size_t)grp * (size_t)g.N * D;     // K, V, dK, dV
+    const size_t qbase = (size_t)grp * (size_t)g.qn * D;    // Q, dO, dQ (row r = token q0 + r)
+    const size_t obase = WHICH == 0 ? qbase : gbase;
+    const int own_n = WHICH == 0 ? g.qn : g.N;
     const float scale = rsqrtf((float)D);
     const T* ownA = WHICH == 0 ? Q : K;
     const T* ownB = WHICH == 0 ? dO : V;
 
-    // range of partner rows each own row interacts with: keys of a query, or queries of a key
+    // range of partner tokens each own row interacts with: keys of a query, or the share's
+    // queries of a key
     if (tid < kSmRows) {
-        const int i = r0 + tid;
+        const int i = (WHICH == 0 ? g.q0 : 0) + r0 + tid;   // this row's token
         int lo = 0, hi = 0;
-        if (i < g.N) {
+        if (r0 + tid < own_n) {
             lo = 0; hi = g.N;
             for (int k = 0; k < g.n_seqs; ++k)
                 if (g.cu[k] <= i && i < g.cu[k + 1]) { lo = g.cu[k]; hi = g.cu[k + 1]; }
             if (causal) { if (WHICH == 0) hi = i + 1; else lo = i; }
+            if (WHICH == 1) { lo = max(lo, g.q0); hi = min(hi, g.q0 + g.qn); }
         }
         sLo[tid] = lo; sHi[tid] = hi;
     }
     for (int idx = tid; idx < kSmRows * D; idx += kThreads) {
         const int r = idx / D, a = idx % D;
-        const bool ok = r0 + r < g.N;
-        sA[r][a] = ok ? ld(ownA + gbase + (size_t)(r0 + r) * D + a) : 0.f;
-        sB[r][a] = ok ? ld(ownB + gbase + (size_t)(r0 + r) * D + a) : 0.f;
+        const bool ok = r0 + r < own_n;
+        sA[r][a] = ok ? ld(ownA + obase + (size_t)(r0 + r) * D + a) : 0.f;
+        sB[r][a] = ok ? ld(ownB + obase + (size_t)(r0 + r) * D + a) : 0.f;
     }
     __syncthreads();
     int plo = g.N, phi = 0;
     for (int r = 0; r < kSmRows; ++r) { plo = min(plo, sHi[r] > sLo[r] ? sLo[r] : g.N); phi = max(phi, sHi[r]); }
+    // partner arrays: keys (absolute rows of K, V) or queries (rows of Q, dO relative to q0)
+    const size_t pbase = WHICH == 0 ? gbase : qbase;
+    const int poff = WHICH == 0 ? 0 : g.q0;
+    const int pend = WHICH == 0 ? g.N : g.q0 + g.qn;
 
     const int myr = tid / TPR, c0 = tid % TPR;
     float acc1[CPT], acc2[CPT];     // dQ (acc1) or dK (acc1), dV (acc2)
@@ -510,28 +520,28 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_generic_kernel(
             const int r = idx % kSmRows, j = idx / kSmRows, pr = p0 + j;     // own row r, partner row pr
             float pv = 0.f, ds = 0.f;
             if (pr >= sLo[r] && pr < sHi[r]) {
-                // query index qi and key index kj of this pair
-                const int qi = WHICH == 0 ? r0 + r : pr;
-                const T* prA = (WHICH == 0 ? K : Q) + gbase + (size_t)pr * D;   // partner k (or q)
-                const T* prB = (WHICH == 0 ? V : dO) + gbase + (size_t)pr * D;  // partner v (or dO)
+                // local query row of this pair
+                const int qi = WHICH == 0 ? r0 + r : pr - g.q0;
+                const T* prA = (WHICH == 0 ? K : Q) + pbase + (size_t)(pr - poff) * D;   // partner k (or q)
+                const T* prB = (WHICH == 0 ? V : dO) + pbase + (size_t)(pr - poff) * D;  // partner v (or dO)
                 float sdot = 0.f, dpdot = 0.f;
                 for (int e = 0; e < D; ++e) {
                     sdot = fmaf(sA[r][e], ld(prA + e), sdot);     // q . k
                     dpdot = fmaf(sB[r][e], ld(prB + e), dpdot);   // dO . v
                 }
-                pv = expf(sdot * scale - LSE[(size_t)grp * g.N + qi]);
-                ds = pv * (dpdot - delta[(size_t)grp * g.N + qi]);
+                pv = expf(sdot * scale - LSE[(size_t)grp * g.qn + qi]);
+                ds = pv * (dpdot - delta[(size_t)grp * g.qn + qi]);
             }
             sP[r][j] = pv;
             sDS[r][j] = ds;
         }
         __syncthreads();
         {
-            const int np = min(kSmKeys, g.N - p0);
+            const int np = min(kSmKeys, pend - p0);
             for (int j = 0; j < np; ++j) {
                 const float ds = sDS[myr][j] * scale, pv = sP[myr][j];
-                const T* xr = (WHICH == 0 ? K : Q) + gbase + (size_t)(p0 + j) * D;
-                const T* yr = dO + gbase + (size_t)(p0 + j) * D;
+                const T* xr = (WHICH == 0 ? K : Q) + pbase + (size_t)(p0 + j - poff) * D;
+                const T* yr = dO + qbase + (size_t)(p0 + j - g.q0) * D;   // read only when WHICH == 1
 #pragma unroll
                 for (int u = 0; u < CPT; ++u) {
                     acc1[u] = fmaf(ds, ld(xr + c0 + u * TPR), acc1[u]);
@@ -541,10 +551,10 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_generic_kernel(
         }
         __syncthreads();
     }
-    if (r0 + myr < g.N) {
+    if (r0 + myr < own_n) {
 #pragma unroll
         for (int u = 0; u < CPT; ++u) {
-            const size_t o = gbase + (size_t)(r0 + myr) * D + c0 + u * TPR;
+            const size_t o = obase + (size_t)(r0 + myr) * D + c0 + u * TPR;
             if (WHICH == 0) st(dQ + o, acc1[u]);
             else { st(dK + o, acc1[u]); st(dV + o, acc2[u]); }
         }
@@ -556,12 +566,12 @@ hipError_t softmax_bwd_generic_TD(const Geom& g, const T* Q, const T* K, const T
                                   const float* LSE, const float* delta, T* dQ, T* dK, T* dV, int causal,
                                   hipStream_t st)
 {
-    dim3 grid((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
-    if (dQ)
-        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 0>), grid, block, 0, st, g, Q, K, V, dO, LSE,
+    dim3 gridq((g.qn + kSmRows - 1) / kSmRows, g.G), gridk((g.N + kSmRows - 1) / kSmRows, g.G), block(kThreads);
+    if (dQ && g.qn > 0)
+        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 0>), gridq, block, 0, st, g, Q, K, V, dO, LSE,
                            delta, dQ, dK, dV, causal);
     if (dK)
-        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 1>), grid, block, 0, st, g, Q, K, V, dO, LSE,
+        hipLaunchKernelGGL((softmax_bwd_generic_kernel<T, D, 1>), gridk, block, 0, st, g, Q, K, V, dO, LSE,
                            delta, dQ, dK, dV, causal);
     return hipGetLastError();
 }
@@ -661,7 +671,8 @@ hipError_t launch_softmax_fwd_generic(const Geom& g, int dtype, const void* Q, c
 hipError_t launch_softmax_delta(const Geom& g, int dtype, const void* O, const void* dO, const float* LSE,
                                 float* delta, float* lse2, hipStream_t st)
 {
-    const size_t rows = (size_t)g.G * (size_t)g.N;
+    const size_t rows = (size_t)g.G * (size_t)g.qn;
+    if (rows == 0) return hipSuccess;
     dim3 grid((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64))), block(kThreads);
     if (dtype == LASP2_F32)
         hipLaunchKernelGGL(softmax_delta_kernel<float>, grid, block, 0, st, g, static_cast<const float*>(O),

@@ -1255,16 +1255,19 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     // Units (group, query block) are numbered group-major with the later (for a causal mask:
     // heavier) query blocks first, and each XCD takes a contiguous range of them, so that the
     // workgroups resident on an XCD mostly share a group's keys in its L2.
-    const int nqb = (g.N + SM_QB - 1) / SM_QB;
+    const int nqb = (g.qn + SM_QB - 1) / SM_QB;
     const unsigned units = (unsigned)g.G * (unsigned)nqb;
     const unsigned per_xcd = (units + 7u) / 8u;
     const unsigned unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
     if ((blockIdx.x >> 3) >= per_xcd || unit >= units) return;
     const int grp = (int)(unit / (unsigned)nqb);
     const int qb = nqb - 1 - (int)(unit % (unsigned)nqb);
-    const int r0 = qb * SM_QB;                       // first query of the workgroup
-    const int rlast = min(r0 + SM_QB, g.N) - 1;
-    const size_t base = (size_t)grp * g.N * ROWB;
+    const int rl0 = qb * SM_QB;                      // first query row of the workgroup (row of Q, O)
+    const int qend = g.q0 + g.qn;                    // one past the last query token of the call
+    const int r0 = g.q0 + rl0;                       // ... as a token of the sequence
+    const int rlast = min(r0 + SM_QB, qend) - 1;
+    const size_t base = (size_t)grp * g.N * ROWB;    // K, V
+    const size_t qbase = (size_t)grp * g.qn * ROWB;  // Q, O
 
     // key range of the workgroup (uniform) and bounds of this lane's query
     int blo, bhi, tmp;
@@ -1273,12 +1276,12 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     if (causal) bhi = rlast + 1;
     const int qi = r0 + 32 * w + l32;                // this lane's query
     int lo_i = 0, hi_i = 0;                          // empty range for rows past the end
-    if (qi < g.N) {
+    if (qi < qend) {
         doc_range(g, qi, lo_i, hi_i);
         if (causal) hi_i = qi + 1;
     }
     // bounds over the wave's valid queries, for the per-tile decision
-    const bool valid = qi < g.N;
+    const bool valid = qi < qend;
     const int lo_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? lo_i : g.N));
     const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_i : 0));
     const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_i : g.N));
@@ -1319,7 +1322,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     // this wave's 32 queries as B-operand fragments (column = query, k = d); zero past the end
     bf16x8 qf[8];
     {
-        const char* p = Q + base + (size_t)min(qi, g.N - 1) * ROWB + 16 * h;
+        const char* p = Q + qbase + (size_t)(min(qi, qend - 1) - g.q0) * ROWB + 16 * h;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const u32x4 z = {0u, 0u, 0u, 0u};
@@ -1433,10 +1436,10 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
     // normalise, write the log-sum-exp, store through the wave's LDS patch
     const float ltot = lsum + xor32(lsum);
     const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
-    if (valid && h == 0) LSE[(size_t)grp * g.N + qi] = (m + log2f(ltot)) * 0.6931471805599453f;
+    if (valid && h == 0) LSE[(size_t)grp * g.qn + (qi - g.q0)] = (m + log2f(ltot)) * 0.6931471805599453f;
     {
         char* stg = sO + w * 4096;
-        const int rbase = r0 + 32 * w;
+        const int rbase = rl0 + 32 * w;
 #pragma unroll
         for (int hv = 0; hv < 2; ++hv) {
 #pragma unroll
@@ -1451,8 +1454,8 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_fwd_mfma_kernel(Geom g, co
             for (int i = 0; i < 4; ++i) {
                 const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
-                if (rbase + row < g.N)
-                    *reinterpret_cast<u32x4*>(O + base + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                if (rbase + row < g.qn)
+                    *reinterpret_cast<u32x4*>(O + qbase + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
             }
         }
     }
@@ -1478,23 +1481,26 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, l32 = lane & 31;
-    const int nqb = (g.N + SM_QB - 1) / SM_QB;
+    const int nqb = (g.qn + SM_QB - 1) / SM_QB;
     const unsigned units = (unsigned)g.G * (unsigned)nqb;
     const unsigned per_xcd = (units + 7u) / 8u;
     const unsigned unit = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
     if ((blockIdx.x >> 3) >= per_xcd || unit >= units) return;
     const int grp = (int)(unit / (unsigned)nqb);
     const int qb = nqb - 1 - (int)(unit % (unsigned)nqb);
-    const int r0 = qb * SM_QB;
-    const int rlast = min(r0 + SM_QB, g.N) - 1;
-    const size_t base = (size_t)grp * g.N * ROWB;
+    const int rl0 = qb * SM_QB;                      // first query row (row of Q, dO, dQ)
+    const int qend = g.q0 + g.qn;
+    const int r0 = g.q0 + rl0;                       // ... as a token of the sequence
+    const int rlast = min(r0 + SM_QB, qend) - 1;
+    const size_t base = (size_t)grp * g.N * ROWB;    // K, V
+    const size_t qbase = (size_t)grp * g.qn * ROWB;  // Q, dO, dQ
 
     int blo, bhi, tmp;
     doc_range(g, r0, blo, tmp);
     doc_range(g, rlast, tmp, bhi);
     if (causal) bhi = rlast + 1;
     const int qi = r0 + 32 * w + l32;
-    const bool valid = qi < g.N;
+    const bool valid = qi < qend;
     int lo_i = 0, hi_i = 0;
     if (valid) {
         doc_range(g, qi, lo_i, hi_i);
@@ -1535,7 +1541,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
     // this wave's 32 queries and their dO rows as B-operand fragments; zero past the end
     bf16x8 qf[8], gf[8];
     {
-        const size_t ro = base + (size_t)min(qi, g.N - 1) * ROWB + 16 * h;
+        const size_t ro = qbase + (size_t)(min(qi, qend - 1) - g.q0) * ROWB + 16 * h;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const u32x4 z = {0u, 0u, 0u, 0u};
@@ -1545,7 +1551,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
             gf[ks] = __builtin_bit_cast(bf16x8, valid ? y : z);
         }
     }
-    const size_t li = (size_t)grp * g.N + min(qi, g.N - 1);
+    const size_t li = (size_t)grp * g.qn + (min(qi, qend - 1) - g.q0);
     const float lse2 = LSE[li] * 1.4426950408889634f;   // log2 of the row's sum of exponentials
     const float dlt = delta[li];
 
@@ -1638,7 +1644,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 
     {
         char* stg = sO + w * 4096;
-        const int rbase = r0 + 32 * w;
+        const int rbase = rl0 + 32 * w;
 #pragma unroll
         for (int hv = 0; hv < 2; ++hv) {
 #pragma unroll
@@ -1654,8 +1660,8 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
             for (int i = 0; i < 4; ++i) {
                 const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
-                if (rbase + row < g.N)
-                    *reinterpret_cast<u32x4*>(dQ + base + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                if (rbase + row < g.qn)
+                    *reinterpret_cast<u32x4*>(dQ + qbase + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
             }
         }
     }
@@ -1704,40 +1710,48 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     const int kb = (int)(unit % (unsigned)nkb);     // causal: the first key blocks see the most queries
     const int c0 = kb * SK_KB;
     const int clast = min(c0 + SK_KB, g.N) - 1;
-    const size_t base = (size_t)grp * g.N * ROWB;
+    const size_t base = (size_t)grp * g.N * ROWB;    // K, V, dK, dV
+    const size_t qbase = (size_t)grp * g.qn * ROWB;  // Q, dO (row r = token q0 + r)
+    const int qend = g.q0 + g.qn;
 
-    // queries this workgroup must visit, and per key (lane) the queries that attend to it
+    // queries this workgroup must visit (those of the call's share only), and per key (lane) the
+    // queries that attend to it
     int blo, bhi, tmp;
     doc_range(g, c0, blo, tmp);
     doc_range(g, clast, tmp, bhi);
     if (causal) blo = c0;
+    blo = max(blo, g.q0);
+    bhi = min(bhi, qend);
     const int kj = c0 + 32 * w + l32;
     const bool valid = kj < g.N;
     int lo_j = 0, hi_j = 0;
     if (valid) {
         doc_range(g, kj, lo_j, hi_j);
         if (causal) lo_j = kj;
+        lo_j = max(lo_j, g.q0);
+        hi_j = min(hi_j, qend);
     }
     const int lo_max = __builtin_amdgcn_readfirstlane(wave_max_i(valid ? lo_j : g.N));
     const int hi_min = __builtin_amdgcn_readfirstlane(wave_min_i(valid ? hi_j : 0));
 
-    const int qb0 = blo / KB, qb1 = (bhi + KB - 1) / KB;
-    const int NBK = qb1 - qb0;
+    // 64-row blocks of the query-side arrays, counted from the share's first row
+    const int qb0 = (blo - g.q0) / KB;
+    const int NBK = bhi > blo ? (bhi - g.q0 + KB - 1) / KB - qb0 : 0;
     uint32_t dvo[16 / NW];
 #pragma unroll
     for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, lane);
-    const char* lse_g = reinterpret_cast<const char*>(LSE2 + (size_t)grp * g.N);
-    const char* dlt_g = reinterpret_cast<const char*>(delta + (size_t)grp * g.N);
+    const char* lse_g = reinterpret_cast<const char*>(LSE2 + (size_t)grp * g.qn);
+    const char* dlt_g = reinterpret_cast<const char*>(delta + (size_t)grp * g.qn);
     auto issue = [&](int i) {
-        const int st = i % NSTAGE, q0 = (qb0 + i) * KB;
-        dma_block<NW>(Q, dO, base, q0, g.N, sQ + st * STAGE_BYTES, sG + st * STAGE_BYTES, w, lane, dvo);
+        const int st = i % NSTAGE, q0 = (qb0 + i) * KB;     // first row of the block
+        dma_block<NW>(Q, dO, qbase, q0, g.qn, sQ + st * STAGE_BYTES, sG + st * STAGE_BYTES, w, lane, dvo);
         // every wave fetches the stage's 64 log2-domain lse and 64 delta values (the same bytes to the same
         // place), which keeps the number of loads in flight equal across waves
-        const uint32_t vo = 4u * (uint32_t)min(q0 + lane, g.N - 1);
+        const uint32_t vo = 4u * (uint32_t)min(q0 + lane, g.qn - 1);
         dma4(lse_g, vo, lds_addr_of(sL + st * 512));
         dma4(dlt_g, vo, lds_addr_of(sL + st * 512 + 256));
     };
-    issue(0);
+    if (NBK > 0) issue(0);
     if (NBK > 1) issue(1);
 
     // per-lane LDS addresses inside ring slot 0, first half: natural reads of Q and dO tiles
@@ -1794,9 +1808,10 @@ __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     auto block = [&](auto stage_c, int bi) {
         constexpr int ST = decltype(stage_c)::value;
         constexpr uint32_t SO = ST * STAGE_BYTES;
-        const int q0b = (qb0 + bi) * KB;
+        const int row0 = (qb0 + bi) * KB;      // first row of the block in Q, dO
+        const int q0b = g.q0 + row0;           // ... as a token of the sequence
         if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
-        if (q0b + KB > g.N) zero_tail_rows<NW>(q0b, g.N, sQ + SO, sG + SO, w, lane);
+        if (row0 + KB > g.qn) zero_tail_rows<NW>(row0, g.qn, sQ + SO, sG + SO, w, lane);
         __syncthreads();
         if (bi + 2 < NBK) issue(bi + 2);
 
@@ -2074,7 +2089,8 @@ hipError_t launch_softmax_bwd_dq_mfma(const Geom& g, const void* Q, const void* 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_bwd_dq_mfma_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    const unsigned nqb = ((unsigned)g.N + SM_QB - 1) / SM_QB;
+    if (g.qn == 0) return hipSuccess;
+    const unsigned nqb = ((unsigned)g.qn + SM_QB - 1) / SM_QB;
     const unsigned units = (unsigned)g.G * nqb;
     const unsigned gx = 8u * ((units + 7u) / 8u);
     const float scale = 1.f / sqrtf((float)g.d);
@@ -2092,7 +2108,8 @@ hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_fwd_mfma_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    const unsigned nqb = ((unsigned)g.N + SM_QB - 1) / SM_QB;
+    if (g.qn == 0) return hipSuccess;
+    const unsigned nqb = ((unsigned)g.qn + SM_QB - 1) / SM_QB;
     const unsigned units = (unsigned)g.G * nqb;
     const unsigned gx = 8u * ((units + 7u) / 8u);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.d);

@@ -73,6 +73,8 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
             if (desc->decay_host[h] < 0.35f) g->decay_mfma = 0;
     }
     g->N = desc->N;
+    g->q0 = 0;
+    g->qn = desc->N;
     g->d = desc->d;
     g->C = desc->C;
     g->L = L;
@@ -273,15 +275,27 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, con
     return from_hip(launch_rows_state_generic(g, desc->dtype, K, dS, dV, 0, st));   // dV = K dM
 }
 
-int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
-                      void* O, float* LSE, int causal, void* stream)
+// Softmax attention for the queries [q_begin, q_begin + q_len) of the sequence; the entry points
+// without a range are the whole sequence.
+static int softmax_geom(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len, Geom* g, bool* empty)
+{
+    int rc = make_geom(desc, g, empty);
+    if (rc != LASP2_OK) return rc;
+    if (g->decay) return LASP2_ERR_DECAY;   // decay belongs to the linear layers
+    if (q_begin < 0 || q_len < 0 || q_begin + q_len > (int64_t)g->N) return LASP2_ERR_SHAPE;
+    g->q0 = (int32_t)q_begin;
+    g->qn = (int32_t)q_len;
+    return LASP2_OK;
+}
+
+static int softmax_fwd_impl(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len, const void* Q,
+                            const void* K, const void* V, void* O, float* LSE, int causal, void* stream)
 {
     Geom g;
     bool empty = false;
-    int rc = make_geom(desc, &g, &empty);
+    int rc = softmax_geom(desc, q_begin, q_len, &g, &empty);
     if (rc != LASP2_OK) return rc;
-    if (g.decay) return LASP2_ERR_DECAY;   // decay belongs to the linear layers
-    if (empty) return LASP2_OK;
+    if (empty || g.qn == 0) return LASP2_OK;
     rc = check_ptrs({Q, K, V, O, LSE});
     if (rc != LASP2_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
@@ -290,30 +304,20 @@ int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, co
     return from_hip(launch_softmax_fwd_generic(g, desc->dtype, Q, K, V, O, LSE, causal ? 1 : 0, st));
 }
 
-int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
-{
-    if (!bytes) return LASP2_ERR_NULL;
-    Geom g;
-    bool empty = false;
-    int rc = make_geom(desc, &g, &empty);
-    if (rc != LASP2_OK) return rc;
-    *bytes = 2 * (size_t)g.G * (size_t)g.N * sizeof(float);   // delta, and the log-sum-exp in base 2
-    return LASP2_OK;
-}
-
-int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
-                      const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
-                      void* workspace, size_t workspace_bytes, int causal, void* stream)
+static int softmax_bwd_impl(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len, const void* Q,
+                            const void* K, const void* V, const void* O, const void* dO, const float* LSE,
+                            void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                            int causal, void* stream)
 {
     Geom g;
     bool empty = false;
-    int rc = make_geom(desc, &g, &empty);
+    int rc = softmax_geom(desc, q_begin, q_len, &g, &empty);
     if (rc != LASP2_OK) return rc;
-    if (g.decay) return LASP2_ERR_DECAY;
     if (empty) return LASP2_OK;
-    rc = check_ptrs({Q, K, V, O, dO, LSE, dQ, dK, dV, workspace});
+    // with no queries dK and dV are still written (zeros); the query-side arrays are not touched
+    rc = g.qn == 0 ? check_ptrs({K, V, dK, dV}) : check_ptrs({Q, K, V, O, dO, LSE, dQ, dK, dV, workspace});
     if (rc != LASP2_OK) return rc;
-    const size_t rows = (size_t)g.G * (size_t)g.N;
+    const size_t rows = (size_t)g.G * (size_t)g.qn;
     if (workspace_bytes < 2 * rows * sizeof(float)) return LASP2_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     float* delta = static_cast<float*>(workspace);
@@ -328,6 +332,51 @@ int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, co
     }
     return from_hip(launch_softmax_bwd_generic(g, desc->dtype, Q, K, V, dO, LSE, delta, dQ, dK, dV,
                                                causal ? 1 : 0, st));
+}
+
+int lasp2_softmax_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                      void* O, float* LSE, int causal, void* stream)
+{
+    return softmax_fwd_impl(desc, 0, desc ? desc->N : 0, Q, K, V, O, LSE, causal, stream);
+}
+
+int lasp2_softmax_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
+{
+    return lasp2_softmax_share_workspace_size(desc, desc ? desc->N : 0, bytes);
+}
+
+int lasp2_softmax_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                      const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                      void* workspace, size_t workspace_bytes, int causal, void* stream)
+{
+    return softmax_bwd_impl(desc, 0, desc ? desc->N : 0, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace,
+                            workspace_bytes, causal, stream);
+}
+
+int lasp2_softmax_fwd_share(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len, const void* Q_t,
+                            const void* K, const void* V, void* O_t, float* LSE_t, int causal, void* stream)
+{
+    return softmax_fwd_impl(desc, q_begin, q_len, Q_t, K, V, O_t, LSE_t, causal, stream);
+}
+
+int lasp2_softmax_share_workspace_size(const lasp2_desc_t* desc, int64_t q_len, size_t* bytes)
+{
+    if (!bytes) return LASP2_ERR_NULL;
+    Geom g;
+    bool empty = false;
+    int rc = softmax_geom(desc, 0, q_len, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    *bytes = 2 * (size_t)g.G * (size_t)g.qn * sizeof(float);   // delta, and the log-sum-exp in base 2
+    return LASP2_OK;
+}
+
+int lasp2_softmax_bwd_share(const lasp2_desc_t* desc, int64_t q_begin, int64_t q_len, const void* Q_t,
+                            const void* K, const void* V, const void* O_t, const void* dO_t,
+                            const float* LSE_t, void* dQ_t, void* dK, void* dV, void* workspace,
+                            size_t workspace_bytes, int causal, void* stream)
+{
+    return softmax_bwd_impl(desc, q_begin, q_len, Q_t, K, V, O_t, dO_t, LSE_t, dQ_t, dK, dV, workspace,
+                            workspace_bytes, causal, stream);
 }
 
 const char* lasp2_status_string(int status)

@@ -22,6 +22,11 @@ struct Geom {
     int32_t H;            // heads (group g uses decay[g % H])
     const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
     int32_t decay_mfma;   // host decision: every factor is large enough for the MFMA decay kernels
+    // Softmax attention only: the queries of one call are the tokens [q0, q0 + qn) of the
+    // sequence (one rank's share; the whole sequence is q0 = 0, qn = N).  Arrays on the query
+    // side (Q, O, LSE, dO, dQ, delta) then have qn rows per group, row r holding token q0 + r;
+    // K, V, dK, dV always have N rows.
+    int32_t q0, qn;
 };
 
 // log2 of the decay factor of group grp (0 when there is no decay): lam^e = exp2f(e * log2 lam).

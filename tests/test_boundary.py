@@ -34,7 +34,8 @@ def test_header_symbols_are_exported():
     assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
             "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string", "lasp2_state_total",
             "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd", "lasp2_softmax_bwd",
-            "lasp2_softmax_workspace_size"} <= names
+            "lasp2_softmax_workspace_size", "lasp2_softmax_fwd_share", "lasp2_softmax_bwd_share",
+            "lasp2_softmax_share_workspace_size"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lasp2.h but not exported"
@@ -131,6 +132,18 @@ def test_null_and_alignment_errors_reach_no_device():
         a = [FAKE] * 10; a[i] = None
         assert lib.lasp2_softmax_bwd(r, *a, ctypes.c_size_t(1 << 40), 1, None) == -1
     assert lib.lasp2_softmax_bwd(r, *([FAKE] * 10), ctypes.c_size_t(sneed.value - 1), 1, None) == -5
+    # one rank's share of it: the query range must lie inside the sequence (N = 1024 here)
+    i64 = ctypes.c_int64
+    for qb, ql in ((-1, 10), (0, -1), (1000, 25), (1025, 0)):
+        assert lib.lasp2_softmax_fwd_share(r, i64(qb), i64(ql), *([FAKE] * 5), 1, None) == -2
+        assert lib.lasp2_softmax_bwd_share(r, i64(qb), i64(ql), *([FAKE] * 10), ctypes.c_size_t(1 << 40), 1, None) == -2
+    assert lib.lasp2_softmax_share_workspace_size(r, i64(1025), ctypes.byref(sneed)) == -2
+    assert lib.lasp2_softmax_share_workspace_size(r, i64(100), ctypes.byref(sneed)) == 0 and sneed.value == 2 * (1 * 2 * 100 * 4)
+    assert lib.lasp2_softmax_fwd_share(r, i64(1024), i64(0), *([None] * 5), 1, None) == 0      # no queries: nothing to do
+    for i in range(5):
+        a = [FAKE] * 5; a[i] = None
+        assert lib.lasp2_softmax_fwd_share(r, i64(8), i64(100), *a, 1, None) == -1
+    assert lib.lasp2_softmax_bwd_share(r, i64(8), i64(100), *([FAKE] * 10), ctypes.c_size_t(sneed.value - 1), 1, None) == -5
 
 
 def test_decay_errors():

@@ -77,3 +77,104 @@ def test_bf16_other_d(oracle):
 def test_packed_documents(oracle, dtype, d, causal):
     cu = synth.doc_offsets(7, 1536, 9, mean_len=1536 / 9, min_len=1)
     _run(oracle, 1, 2, 1536, d, dtype, seed=172, causal=causal, cu=cu)
+
+
+def _run_share(oracle, B, H, N, d, dtype, seed, causal, q_begin, q_len, cu=None):
+    """One rank's share: queries [q_begin, q_begin + q_len) against all N keys.  The oracle runs the
+    whole sequence; O, LSE and dQ are compared on the share's rows, and dK, dV against the oracle's
+    gradient for a dO that is zero outside the share (the gradient is linear in dO, and a zero dO
+    row makes that query's dS row zero, so this is exactly the share's contribution)."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+
+    G = B * H
+    x = host_inputs(seed, G, N, d, dtype, names=("Q", "K", "V"))
+    dOh = synth.gen_tensor(seed, "dO", G, N, d, dtype)
+    p = bd.Problem(B, H, N, d, 64, 0, dtype, cu)
+    sl = slice(q_begin, q_begin + q_len)
+    K, V = (to_device(x[n], B, H, dtype) for n in ("K", "V"))
+    Qt = to_device(np.ascontiguousarray(x["Q"][:, sl]), B, H, dtype)
+    dOt = to_device(np.ascontiguousarray(dOh[:, sl]), B, H, dtype)
+    Ot = torch.full_like(Qt, float("nan"))
+    LSEt = torch.full((B, H, q_len), float("nan"), dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_fwd_share(p, q_begin, q_len, Qt, K, V, Ot, LSEt, causal)
+    dQt = torch.full_like(Qt, float("nan"))
+    dK, dV = (torch.full_like(K, float("nan")) for _ in range(2))
+    ws = torch.empty(max(bd.lasp2_softmax_share_workspace_size(p, q_len) // 4, 4), dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_bwd_share(p, q_begin, q_len, Qt, K, V, Ot, dOt, LSEt, dQt, dK, dV, ws, causal)
+    torch.cuda.synchronize()
+
+    x64 = {k: v.astype(np.float64) for k, v in x.items()}
+    O_ref, lse_ref = oracle.softmax_fwd(x64["Q"], x64["K"], x64["V"], causal, cu)
+    dO_masked = np.zeros_like(dOh, dtype=np.float64)
+    dO_masked[:, sl] = dOh[:, sl]
+    dQ_ref, dK_ref, dV_ref = oracle.softmax_bwd(x64["Q"], x64["K"], x64["V"], dO_masked, causal, cu)
+    errs = {}
+    if q_len:
+        errs["O"] = rel_l2(to_host(Ot), O_ref[:, sl])
+        errs["lse_abs"] = float(np.abs(LSEt.cpu().numpy().reshape(G, q_len) - lse_ref[:, sl]).max())
+        errs["dQ"] = rel_l2(to_host(dQt), dQ_ref[:, sl])
+    floor = max(np.linalg.norm(dV_ref), 1e-300)
+    for n, t, r in (("dK", dK, dK_ref), ("dV", dV, dV_ref)):
+        got = to_host(t)
+        assert np.isfinite(got).all(), n      # every row of dK, dV is written
+        errs[n] = rel_l2(got, r) if np.linalg.norm(r) > 1e-9 * floor else float(np.linalg.norm(got) / max(floor, 1.0))
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= ((1e-4 if dtype == "f32" else 2e-2) if k == "lse_abs" else TOL[dtype]), (k, errs)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("q_begin,q_len", [(448, 300), (0, 100), (1400, 100), (37, 211), (1499, 1), (640, 0), (0, 1500)])
+def test_share_bf16_d128(oracle, q_begin, q_len, causal):
+    _run_share(oracle, 1, 2, 1500, 128, "bf16", seed=180, causal=causal, q_begin=q_begin, q_len=q_len)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("q_begin,q_len", [(130, 77), (0, 33), (512, 0)])
+def test_share_fp32(oracle, q_begin, q_len, causal):
+    _run_share(oracle, 2, 2, 600, 32, "f32", seed=181, causal=causal, q_begin=q_begin, q_len=q_len)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_share_packed_documents(oracle, dtype, d, causal):
+    cu = synth.doc_offsets(8, 1536, 7, mean_len=1536 / 7, min_len=1)
+    _run_share(oracle, 1, 2, 1536, d, dtype, seed=182, causal=causal, q_begin=500, q_len=421, cu=cu)
+
+
+def test_shares_add_up_to_the_whole(oracle):
+    """dK and dV of the whole sequence are the sums over ranks of the shares' contributions
+    (what the reduce-scatter of the backward would compute)."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    B, H, N, d, dtype = 1, 2, 1024, 128, "bf16"
+    x = host_inputs(183, B * H, N, d, dtype, names=("Q", "K", "V"))
+    dOh = synth.gen_tensor(183, "dO", B * H, N, d, dtype)
+    p = bd.Problem(B, H, N, d, 64, 0, dtype)
+    Q, K, V, dO = (to_device(a, B, H, dtype) for a in (x["Q"], x["K"], x["V"], dOh))
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_fwd(p, Q, K, V, O, LSE, True)
+    dQ, dK, dV = (torch.empty_like(Q) for _ in range(3))
+    ws = torch.empty(bd.lasp2_softmax_workspace_size(p) // 4, dtype=torch.float32, device="cuda")
+    bd.lasp2_softmax_bwd(p, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, True)
+    sumK = torch.zeros(Q.shape, dtype=torch.float32, device="cuda")
+    sumV = torch.zeros_like(sumK)
+    for r in range(4):
+        a, n = 256 * r, 256
+        Qt, Ot, dOt = (t[:, :, a:a + n].contiguous() for t in (Q, O, dO))
+        Lt = LSE[:, :, a:a + n].contiguous()
+        O2, L2 = torch.empty_like(Qt), torch.empty_like(Lt)
+        bd.lasp2_softmax_fwd_share(p, a, n, Qt, K, V, O2, L2, True)
+        assert torch.equal(O2, Ot) and torch.equal(L2, Lt)          # same kernel, same tiles, same bits
+        dQt, dKt, dVt = torch.empty_like(Qt), torch.empty_like(K), torch.empty_like(K)
+        bd.lasp2_softmax_bwd_share(p, a, n, Qt, K, V, Ot, dOt, Lt, dQt, dKt, dVt, ws, True)
+        assert torch.equal(dQt, dQ[:, :, a:a + n])
+        sumK += dKt.float()
+        sumV += dVt.float()
+    torch.cuda.synchronize()
+    # each share rounds its contribution to bf16 once more than the whole does
+    for s, full in ((sumK, dK), (sumV, dV)):
+        err = float((s - full.float()).norm() / full.float().norm())
+        assert err <= 1e-2, err
