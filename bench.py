@@ -57,23 +57,28 @@ def cpu_baseline(cfg, sample_tokens):
 
 def softmax_main(args):
     """The standard-attention layer of the hybrid model (forward + backward of
-    lasp2_softmax_fwd / lasp2_softmax_bwd), causal, at B=1, H=16, N=32768, d=128: one rank's
-    share when a sequence of that length sits on one GPU.  Priced against the bf16 MFMA peak with
+    lasp2_softmax_fwd_share / lasp2_softmax_bwd_share), causal, B=1, H=16, d=128: by default a
+    whole sequence of 32768 tokens on the one GPU; with --softmax-total T the last rank's share of
+    a T-token sequence (its 32768 queries against all T gathered keys).  Priced against the bf16 MFMA peak with
     the algorithmic flop count on the causal triangle: 2 products forward, 5 backward."""
     import numpy as np
     import torch
     from paper_2502_07563_amd import binding as bd
-    B, H, N, d = 1, 16, args.softmax_len, 128
+    B, H, d = 1, 16, 128
+    n_q = args.softmax_len                       # queries of the call
+    N = args.softmax_total or n_q                # gathered keys; the share is the sequence's last n_q tokens
+    q_begin = N - n_q
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     p = bd.Problem(B, H, N, d, 64, 0, "bf16")
     gen = torch.Generator(device=dev)
     gen.manual_seed(41)
-    mk = lambda: torch.randn((B, H, N, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    Q, K, V, dO = mk(), mk(), mk(), mk()
-    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
-    LSE = torch.empty((B, H, N), dtype=torch.float32, device=dev)
-    ws = torch.empty(bd.lasp2_softmax_workspace_size(p), dtype=torch.uint8, device=dev)
+    mk = lambda n: torch.randn((B, H, n, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    Q, dO, K, V = mk(n_q), mk(n_q), mk(N), mk(N)
+    O, dQ = torch.empty_like(Q), torch.empty_like(Q)
+    dK, dV = torch.empty_like(K), torch.empty_like(K)
+    LSE = torch.empty((B, H, n_q), dtype=torch.float32, device=dev)
+    ws = torch.empty(bd.lasp2_softmax_share_workspace_size(p, n_q), dtype=torch.uint8, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
 
@@ -81,10 +86,10 @@ def softmax_main(args):
         e = [ev() for _ in range(3)] if record else None
         if record:
             e[0].record()
-        bd.lasp2_softmax_fwd(p, Q, K, V, O, LSE, True)
+        bd.lasp2_softmax_fwd_share(p, q_begin, n_q, Q, K, V, O, LSE, True)
         if record:
             e[1].record()
-        bd.lasp2_softmax_bwd(p, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, True)
+        bd.lasp2_softmax_bwd_share(p, q_begin, n_q, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, True)
         if record:
             e[2].record()
             marks.append(e)
@@ -99,13 +104,15 @@ def softmax_main(args):
     dt = time.perf_counter() - t0
     t_fwd = sum(m[0].elapsed_time(m[1]) for m in marks) / len(marks)
     t_bwd = sum(m[1].elapsed_time(m[2]) for m in marks) / len(marks)
-    pairs = B * H * N * (N + 1) / 2.0          # (query, key) pairs inside the causal mask
+    pairs = B * H * (n_q * q_begin + n_q * (n_q + 1) / 2.0)     # (query, key) pairs inside the causal mask
     fl_fwd, fl_bwd = 4.0 * pairs * d, 10.0 * pairs * d
     out = {
-        "metric": "fwd+bwd tokens/s per layer", "value": B * N / (dt / args.steps), "unit": "tokens/s",
+        "metric": "fwd+bwd tokens/s per layer", "value": B * n_q / (dt / args.steps), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"softmax attention layer of the hybrid model: B={B} H={H} N={N} d={d} causal"},
+        "config": {"workload": f"softmax attention layer of the hybrid model: B={B} H={H} N={N} d={d} causal"
+                               + (f", one rank's share: the last {n_q} queries against all {N} gathered keys"
+                                  if q_begin else "")},
         "ms": {"softmax_fwd": t_fwd, "softmax_bwd": t_bwd},
         "roofline": {"bound": "mfma", "kernel": "lasp2_softmax_bwd (delta, dQ and dK/dV kernels; the dK/dV "
                      "kernel dominates)", "achieved": fl_bwd / (t_bwd * 1e-3) / 1e12,
@@ -116,7 +123,7 @@ def softmax_main(args):
     }
     if not args.no_cpu_baseline:
         import oracle
-        n = min(N, 4096)
+        n = min(n_q, 4096)
         rng = np.random.default_rng(41)
         x = [rng.standard_normal((H, n, d)) for _ in range(4)]
         t0 = time.perf_counter()
@@ -124,8 +131,10 @@ def softmax_main(args):
         oracle.softmax_bwd(x[0], x[1], x[2], x[3], True)
         dtc = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": n / dtc, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
-                               "sample": f"fp64 oracle, softmax fwd+bwd, {H} heads x {n} tokens (the rate falls "
-                                         f"as 1/N; at N={N} it would be about {n / dtc * n / N:.1f}), {dtc:.1f} s"}
+                               "sample": f"fp64 oracle, softmax fwd+bwd, {H} heads x {n} tokens, whole sequence "
+                                         f"causal (the rate falls as 1/keys; for this workload's "
+                                         f"{pairs / (B * H * n_q):.0f} keys per query it would be about "
+                                         f"{n / dtc * (n / 2.0) / (pairs / (B * H * n_q)):.1f}), {dtc:.1f} s"}
     print(json.dumps(out))
 
 
@@ -144,7 +153,11 @@ def main():
     ap.add_argument("--softmax", action="store_true",
                     help="time the standard-attention layer of the hybrid model instead (not the headline "
                          "workload): causal softmax attention forward + backward, B=1 H=16 d=128")
-    ap.add_argument("--softmax-len", type=int, default=32768, help="sequence length for --softmax")
+    ap.add_argument("--softmax-len", type=int, default=32768, help="number of queries for --softmax")
+    ap.add_argument("--softmax-total", type=int, default=None,
+                    help="for --softmax: length of the whole gathered sequence; the call then computes one "
+                         "rank's share, the sequence's last --softmax-len queries against all keys "
+                         "(default: the queries are the whole sequence)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

@@ -217,3 +217,53 @@ def test_softmax_attention_bench_configuration(oracle):
         errs[k] = rel_l2(_gpu_group(t, g)[rows], ref)
         assert errs[k] <= TOL[dtype], errs
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+
+
+def test_softmax_last_rank_share_bench_configuration(oracle):
+    """One rank's share at the size `bench.py --softmax --softmax-total 2097152` times: the last
+    32768 queries of a 2M-token sequence against all gathered keys (the 64-rank, 2048K-token setting).
+    Sampled rows of O, LSE and dQ of one head against the definition; dK and dV through identities
+    that hold at any size: sum_j dV_j = sum_i dO_i (rows of P sum to one) and sum_j dK_j = 0
+    (rows of dS sum to zero), and rows no query of the share can see are zero."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    B, H, d, N, n_q = 1, 16, 128, 2097152, 32768
+    q_begin = N - n_q
+    p = bd.Problem(B, H, N, d, 64, 0, "bf16")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(43)
+    mk = lambda n: torch.randn((B, H, n, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Q, dO, K, V = mk(n_q), mk(n_q), mk(N), mk(N)
+    O, dQ = torch.empty_like(Q), torch.empty_like(Q)
+    dK, dV = torch.empty_like(K), torch.empty_like(K)
+    LSE = torch.empty((B, H, n_q), dtype=torch.float32, device="cuda")
+    ws = torch.empty(bd.lasp2_softmax_share_workspace_size(p, n_q), dtype=torch.uint8, device="cuda")
+    bd.lasp2_softmax_fwd_share(p, q_begin, n_q, Q, K, V, O, LSE, True)
+    bd.lasp2_softmax_bwd_share(p, q_begin, n_q, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, True)
+    torch.cuda.synchronize()
+    g = 9
+    f64 = lambda t: t[0, g].float().cpu().numpy().astype(np.float64)
+    Kh, Vh = f64(K), f64(V)
+    Qfull = np.zeros((N, d)); Qfull[q_begin:] = f64(Q)
+    dOfull = np.zeros((N, d)); dOfull[q_begin:] = f64(dO)
+    rng = np.random.default_rng(43)
+    loc = np.unique(np.concatenate([rng.integers(0, n_q, 20), [0, 1, 255, 256, n_q - 1]])).astype(np.int64)
+    rows = loc + q_begin
+    O_ref, lse_ref = oracle.softmax_rows(Qfull, Kh, Vh, rows, True)
+    errs = {"O": rel_l2(f64(O)[loc], O_ref),
+            "LSE": float(np.max(np.abs(LSE[0, g].cpu().numpy()[loc] - lse_ref)))}
+    lse_all = np.zeros(N); lse_all[rows] = lse_ref
+    delta_all = np.zeros(N); delta_all[rows] = np.sum(dOfull[rows] * O_ref, axis=1)
+    dQ_ref = oracle.softmax_bwd_rows(Qfull, Kh, Vh, dOfull, lse_all, delta_all, rows, 0, True)
+    errs["dQ"] = rel_l2(f64(dQ)[loc], dQ_ref)
+    assert errs["O"] <= TOL["bf16"] and errs["LSE"] <= 2e-3 and errs["dQ"] <= TOL["bf16"], errs
+    # identities for dK, dV (fp32 sums on the device over all 2M rows of the head)
+    dVs = dV[0, g].float().sum(dim=0).cpu().numpy()
+    dOs = dO[0, g].float().sum(dim=0).cpu().numpy()
+    dKs = dK[0, g].float().sum(dim=0).cpu().numpy()
+    dK_abs = float(dK[0, g].float().abs().sum())
+    errs["sum dV vs sum dO"] = float(np.linalg.norm(dVs - dOs) / np.linalg.norm(dOs))
+    errs["sum dK / sum |dK|"] = float(np.abs(dKs).sum() / dK_abs)
+    assert errs["sum dV vs sum dO"] <= 2e-2 and errs["sum dK / sum |dK|"] <= 1e-2, errs
+    assert bool(torch.isfinite(dK).all()) and bool(torch.isfinite(dV).all())
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
