@@ -1526,17 +1526,29 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
     // lane offsets of the natural and the transposed reads; the other k-steps and column blocks
     // differ from these only in address bits 5..7, which the row term leaves clear, so they are
     // derived with one XOR at the point of use instead of being held in registers
-    const int nat0 = tile_off(l32, h);
-    int pv0, pv1;
+    // per-lane LDS addresses inside ring slot 0, first half: natural reads of the K and V tiles
+    // (row = key) and transposed reads of the K tile (row = d); slot, half and k-step are added
+    // as immediates at the point of use
+    uint32_t natK[8], natV[8], trK[4][2];
     {
         const int i = lane & 15, g2 = (lane >> 4) & 1;
         const int cl = 16 * g2 + 4 * (i & 3), rl = i >> 2;
-        pv0 = tr_off(4 * h + rl, cl);
-        pv1 = tr_off(8 + 4 * h + rl, cl);
+        const uint32_t aK = lds_addr_of(sK), aV = lds_addr_of(sV);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            natK[ks] = aK + tile_off(l32, 2 * ks + h);
+            natV[ks] = aV + tile_off(l32, 2 * ks + h);
+            pin_vgpr(natK[ks]);
+            pin_vgpr(natV[ks]);
+        }
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) {
+            trK[tv][0] = aK + tr_off(4 * h + rl, 32 * tv + cl);
+            trK[tv][1] = aK + tr_off(8 + 4 * h + rl, 32 * tv + cl);
+            pin_vgpr(trK[tv][0]);
+            pin_vgpr(trK[tv][1]);
+        }
     }
-#define NAT(ks) (nat0 ^ ((ks) << 5))
-#define PV0(tv) (pv0 ^ ((tv) << 6))
-#define PV1(tv) (pv1 ^ ((tv) << 6))
 
     // this wave's 32 queries and their dO rows as B-operand fragments; zero past the end
     bf16x8 qf[8], gf[8];
@@ -1561,9 +1573,12 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
 
-    for (int bi = 0; bi < NBK; ++bi) {
-        char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
-        char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+    // One key block; the ring slot is a compile-time constant (the loop below is unrolled by the
+    // ring length), so every LDS read is a pinned register plus an immediate.
+    auto block = [&](auto stage_c, int bi) {
+        constexpr int ST = decltype(stage_c)::value;
+        char* tK = sK + ST * STAGE_BYTES;
+        char* tV = sV + ST * STAGE_BYTES;
         const int k0b = (kb0 + bi) * KB;
         if (bi + 1 < NBK) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
         if (k0b + KB > g.N) zero_tail_rows<NW>(k0b, g.N, tK, tV, w, lane);
@@ -1576,34 +1591,33 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
             const int k0 = k0b + 32 * half;
             if (k0 >= hi_max || k0 + 32 <= lo_min) continue;
             const bool whole = (k0 >= lo_max) && (k0 + 32 <= hi_min);
-            const char* tKh = tK + half * (32 * ROWB);
-            const char* tVh = tV + half * (32 * ROWB);
+            const uint32_t HO = ST * STAGE_BYTES + half * (32 * ROWB);
             // scores^T = K_tile Q_w^T and dP^T = V_tile dO_w^T (keys x queries)
             f32x16 sc, dp;
 #pragma unroll
             for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tKh, NAT(ks));
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_u(natK[ks] + HO);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tKh, NAT(ks + 4));
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_u(natK[ks + 4] + HO);
             SCHED_FENCE();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
             SCHED_FENCE();
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tVh, NAT(ks));
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_u(natV[ks] + HO);
             SCHED_FENCE();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
             SCHED_FENCE();
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_at(tVh, NAT(ks + 4));
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_u(natV[ks + 4] + HO);
             SCHED_FENCE();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) dp = mfma(bufA[ks], gf[ks], dp);
             SCHED_FENCE();
 #pragma unroll
-            for (int tv = 0; tv < 4; ++tv) bufA[tv] = lds_read_tr8_at(tKh, PV0(tv), PV1(tv));
+            for (int tv = 0; tv < 4; ++tv) bufA[tv] = lds_read_tr8_u(trK[tv][0] + HO, trK[tv][1] + HO);
             SCHED_FENCE();
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) dp = mfma(bufB[ks], gf[ks + 4], dp);
@@ -1624,7 +1638,7 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
             }
             SCHED_FENCE();
 #pragma unroll
-            for (int tv = 0; tv < 4; ++tv) bufB[tv] = lds_read_tr8_at(tKh + 16 * ROWB, PV0(tv), PV1(tv));
+            for (int tv = 0; tv < 4; ++tv) bufB[tv] = lds_read_tr8_u(trK[tv][0] + (HO + 16 * ROWB), trK[tv][1] + (HO + 16 * ROWB));
             SCHED_FENCE();
             {
                 u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
@@ -1640,6 +1654,12 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
             }
             SCHED_FENCE();
         }
+    };
+    static_assert(NSTAGE == 3, "the block loop is unrolled by the ring length");
+    for (int bi = 0; bi < NBK; bi += 3) {
+        block(std::integral_constant<int, 0>{}, bi);
+        if (bi + 1 < NBK) block(std::integral_constant<int, 1>{}, bi + 1);
+        if (bi + 2 < NBK) block(std::integral_constant<int, 2>{}, bi + 2);
     }
 
     {
@@ -1666,9 +1686,6 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
         }
     }
 }
-#undef NAT
-#undef PV0
-#undef PV1
 
 // =====================================================================================
 // Softmax attention backward, dK and dV: one workgroup of four waves per 128 keys (32 per wave,
