@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblasp2.so")
-SOURCES = ["lasp2_api.hip", "kernels_generic.hip", "kernels_mfma.hip"]
+SOURCES = ["lasp2_api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_softmax.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -95,3 +95,46 @@ def test_no_compiler_placed_vmcnt_wait_in_the_walk(isa):
                 in_asm = False
             elif "vmcnt" in l and i > first_barrier:
                 assert in_asm, (cname, i, l.strip())
+
+
+@pytest.fixture(scope="module")
+def isa_softmax(tmp_path_factory):
+    from paper_2502_07563_amd import build as b
+    out = tmp_path_factory.mktemp("isa_sm") / "kernels_softmax.s"
+    flags = [f for f in b.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), *flags, "-S", "--cuda-device-only",
+           "-o", str(out), os.path.join(SRC, "kernels_softmax.hip")]
+    subprocess.run(cmd, check=True, capture_output=True)
+    return open(out).read().split("\n")
+
+
+def test_softmax_kernels_keep_their_stage_loads_in_flight(isa_softmax):
+    """The softmax kernels count their direct-to-LDS stage loads by hand as well.  A register spill
+    inside their loops would be reloaded with a vector-memory load, for which the compiler waits
+    with vmcnt(0): that drains every stage load in flight (seen once: the dQ kernel lost 13 %).
+    So: no scratch memory at all, and after the first barrier no vmcnt wait outside the kernels'
+    own asm blocks."""
+    text = "\n".join(isa_softmax)
+    found = 0
+    for i, l in enumerate(isa_softmax):
+        m = re.match(r"^(_ZN.*(softmax_fwd_mfma_kernel|softmax_bwd_dq_mfma_kernel|softmax_bwd_dkv_mfma_kernel).*):", l)
+        if not m:
+            continue
+        found += 1
+        sym, name = m.group(1), m.group(2)
+        end = next(j for j in range(i, len(isa_softmax)) if "s_endpgm" in isa_softmax[j])
+        body = isa_softmax[i:end]
+        assert not any("scratch_" in x for x in body), f"{name} touches scratch memory"
+        k = re.search(r"\.amdhsa_kernel " + re.escape(sym) + r".*?\.amdhsa_private_segment_fixed_size (\d+)",
+                      text, flags=re.S)
+        assert k and int(k.group(1)) == 0, f"{name} has a private segment"
+        first_barrier = next(j for j, x in enumerate(body) if "s_barrier" in x)
+        in_asm = False
+        for j, x in enumerate(body):
+            if "#ASMSTART" in x:
+                in_asm = True
+            elif "#ASMEND" in x:
+                in_asm = False
+            elif "vmcnt" in x and j > first_barrier:
+                assert in_asm, (name, j, x.strip())
+    assert found == 3
