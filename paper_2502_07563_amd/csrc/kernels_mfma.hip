@@ -46,14 +46,14 @@ __device__ __forceinline__ void store_block(const BlockRegs<NT>& r, char* tx, ch
 }
 
 // acc[u] += X_blk^T Y_blk restricted to the 32x32 tile (a, b) = ((t0+u)/4, (t0+u)%4) of the
-// d x d state, for the 64 tokens of one LDS stage.
-template <int TPW>
+// d x d state, for the NTOK tokens at the head of an LDS tile.
+template <int TPW, int NTOK = KB>
 __device__ __forceinline__ void update_tiles(f32x16 (&acc)[TPW], const char* tx, const char* ty,
                                              int t0, int lane)
 {
     const int h = lane >> 5;
 #pragma unroll
-    for (int ks = 0; ks < KB / 16; ++ks) {
+    for (int ks = 0; ks < NTOK / 16; ++ks) {
         const int rA = 16 * ks + 8 * h, rB = rA + 4;
         bf16x8 aop[TPW];
 #pragma unroll
@@ -89,18 +89,27 @@ __device__ __forceinline__ u32x4 scale_bf16x8(u32x4 x, float w)
 // With decay (DECAY) the rows of X carry the token's weight lam^(slot end - token), or
 // lam^(token - slot start) when anchor_start is set; the weighted row is rounded to bf16
 // before the product, like every other operand of the matrix cores.
+//
+// The kernel only reads (2 x 256 bytes per token against 64 KiB written per slot) and does
+// little arithmetic per byte.  It streams the slot through a ring of five 32-token stages
+// (80 KiB of LDS, so that two workgroups share a CU and one's start-up and final store hide
+// under the other's stream), filled by direct global->LDS loads marked non-temporal (the data
+// is read once): four stages are on their way while a fifth is consumed.
 // =====================================================================================
-constexpr int ST_NW = 8, ST_NT = ST_NW * 64, ST_TPW = 16 / ST_NW;
+constexpr int ST_NW = 8, ST_NT = ST_NW * 64, ST_TPW = 16 / ST_NW, ST_NST = 5;
+constexpr int ST_KB = 32, ST_STAGE = ST_KB * ROWB;   // tokens and bytes (per tensor) of a stage
 
 template <bool DECAY>
 __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* __restrict__ X,
                                                             const char* __restrict__ Y,
                                                             float* __restrict__ M, int anchor_start)
 {
+    constexpr int DPS = 2;   // loads per wave per stage: one instruction (four rows) per tensor
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* sX = smem;                     // 2 stages
-    char* sY = smem + 2 * STAGE_BYTES;   // 2 stages
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    char* sX = smem;                       // ST_NST stages
+    char* sY = smem + ST_NST * ST_STAGE;   // ST_NST stages
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = blockIdx.x, grp = blockIdx.y;
     int tok0, len;
     slot_range(g, s, tok0, len);
@@ -112,25 +121,48 @@ __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
 
-    const int nblk = (len + KB - 1) / KB;
-    const float l2 = DECAY ? decay_log2(g, grp) : 0.f;
-    BlockRegs<ST_NT> regs;
-    load_block<ST_NT>(regs, X, Y, row0, 0, len, tid);
+    const int nblk = (len + ST_KB - 1) / ST_KB;
+    float l2 = DECAY ? decay_log2(g, grp) : 0.f;
+    asm volatile("" : "+v"(l2));   // first use here, not inside the loop (where the compiler's wait for it would drain the ring)
+    // wave w fetches rows 4w .. 4w+3 of a stage: lane l the 16 bytes that land swizzled at its place
+    const int myrow = 4 * w + (lane >> 4);
+    const uint32_t dvo = dma_lane_off(w, lane);
+    auto issue = [&](int i, int slot) {
+        const int tok = i * ST_KB;
+        const size_t blk = row0 + (size_t)tok * ROWB;
+        // rows past the slot's end fetch its last row (always in bounds) and are zeroed after landing
+        const uint32_t voff = (uint32_t)(min(myrow, len - 1 - tok) * ROWB) + (dvo & (ROWB - 1));
+        dma16_nt(X + blk, voff, lds_addr_of(sX + slot * ST_STAGE + 4 * w * ROWB));
+        dma16_nt(Y + blk, voff, lds_addr_of(sY + slot * ST_STAGE + 4 * w * ROWB));
+    };
+    for (int i = 0; i < ST_NST - 1 && i < nblk; ++i) issue(i, i);
+
+    int slot = 0, fill = ST_NST - 1;   // slot of the block consumed now, and of the next block issued
     for (int blk = 0; blk < nblk; ++blk) {
-        char* tx = sX + (blk & 1) * STAGE_BYTES;
-        char* ty = sY + (blk & 1) * STAGE_BYTES;
-        if (DECAY) {
-#pragma unroll
-            for (int u = 0; u < BlockRegs<ST_NT>::LPT; ++u) {
-                const int tok = blk * KB + ((tid + u * ST_NT) >> 4);
-                const float wt = exp2f((float)(anchor_start ? tok : len - 1 - tok) * l2);
-                regs.x[u] = scale_bf16x8(regs.x[u], wt);
-            }
+        char* tx = sX + slot * ST_STAGE;
+        char* ty = sY + slot * ST_STAGE;
+        // this wave's loads of block blk have landed once at most the later blocks' are outstanding
+        const int later = min(nblk - 1 - blk, ST_NST - 2);
+        if (later >= 3) wait_vmcnt<3 * DPS>();
+        else if (later == 2) wait_vmcnt<2 * DPS>();
+        else if (later == 1) wait_vmcnt<DPS>();
+        else wait_vmcnt<0>();
+        const int tok = blk * ST_KB + myrow;
+        u32x4* px = reinterpret_cast<u32x4*>(tx + myrow * ROWB + (lane & 15) * 16);
+        if (tok >= len) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            *px = z;
+            *reinterpret_cast<u32x4*>(ty + myrow * ROWB + (lane & 15) * 16) = z;
+        } else if (DECAY) {
+            // weight this wave's own rows of the X tile (a row takes one weight: the swizzle does not matter)
+            const float wt = exp2f((float)(anchor_start ? tok : len - 1 - tok) * l2);
+            *px = scale_bf16x8(*px, wt);
         }
-        store_block<ST_NT>(regs, tx, ty, tid);
-        if (blk + 1 < nblk) load_block<ST_NT>(regs, X, Y, row0, (blk + 1) * KB, len, tid);
-        __syncthreads();
-        update_tiles<ST_TPW>(acc, tx, ty, w * ST_TPW, lane);
+        __syncthreads();   // block complete in LDS; every wave has left the block before it
+        if (blk + ST_NST - 1 < nblk) issue(blk + ST_NST - 1, fill);
+        update_tiles<ST_TPW, ST_KB>(acc, tx, ty, w * ST_TPW, lane);
+        slot = slot + 1 == ST_NST ? 0 : slot + 1;
+        fill = fill + 1 == ST_NST ? 0 : fill + 1;
     }
 
     float* m = M + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
@@ -1001,7 +1033,7 @@ bool mfma_path_supported(const Geom& g, int dtype)
 hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float* M, int anchor_start,
                               hipStream_t st)
 {
-    constexpr int smem = 4 * STAGE_BYTES;   // 64 KiB
+    constexpr int smem = 2 * ST_NST * ST_STAGE;   // 80 KiB: two workgroups per CU
     auto kern = g.decay ? states_mfma_kernel<true> : states_mfma_kernel<false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);

@@ -131,6 +131,12 @@ __device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
 
+// The same load marked non-temporal, for data that is read exactly once.
+__device__ __forceinline__ void dma16_nt(const char* sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+
 // Byte offset, inside a block of rows that starts at a multiple of 16, of the 16 bytes that lane
 // `lane` of wave instruction `k` (rows 4k .. 4k+3) must fetch so that they land swizzled.
 __device__ __forceinline__ uint32_t dma_lane_off(int k, int lane)
@@ -143,7 +149,7 @@ __device__ __forceinline__ uint32_t dma_lane_off(int k, int lane)
 // stage tiles tx, ty; dvo[u] = dma_lane_off(w * IPW + u, lane), computed once per kernel.
 // Rows past the slot's end are fetched from its last row (always in bounds) and zeroed
 // afterwards by zero_tail_rows().
-template <int NW>
+template <int NW, bool STREAM = false>
 __device__ __forceinline__ void dma_block(const char* X, const char* Y, size_t row0_bytes, int tok,
                                           int len, char* tx, char* ty, int w, int lane,
                                           const uint32_t (&dvo)[16 / NW])
@@ -159,8 +165,13 @@ __device__ __forceinline__ void dma_block(const char* X, const char* Y, size_t r
             const int r = 4 * k + (lane >> 4);
             voff = (uint32_t)(min(r, len - 1 - tok) * ROWB + (int)(voff & (ROWB - 1)));
         }
-        dma16(X + blk, voff, lds_addr_of(tx + 4 * k * ROWB));
-        dma16(Y + blk, voff, lds_addr_of(ty + 4 * k * ROWB));
+        if (STREAM) {
+            dma16_nt(X + blk, voff, lds_addr_of(tx + 4 * k * ROWB));
+            dma16_nt(Y + blk, voff, lds_addr_of(ty + 4 * k * ROWB));
+        } else {
+            dma16(X + blk, voff, lds_addr_of(tx + 4 * k * ROWB));
+            dma16(Y + blk, voff, lds_addr_of(ty + 4 * k * ROWB));
+        }
     }
 }
 
