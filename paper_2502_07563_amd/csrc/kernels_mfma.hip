@@ -4,6 +4,7 @@
 // state slot and carries the running d x d state in fp32 MFMA accumulators.  Operand
 // conventions, the LDS tile layout and the stage loads are described in mfma_tile.h.
 #include "mfma_tile.h"
+#include <algorithm>
 
 namespace lasp2 {
 namespace {
@@ -94,7 +95,8 @@ __device__ __forceinline__ u32x4 scale_bf16x8(u32x4 x, float w)
 // little arithmetic per byte.  It streams the slot through a ring of five 32-token stages
 // (80 KiB of LDS, so that two workgroups share a CU and one's start-up and final store hide
 // under the other's stream), filled by direct global->LDS loads marked non-temporal (the data
-// is read once): four stages are on their way while a fifth is consumed.
+// is read once): four stages are on their way while a fifth is consumed.  The grid is two
+// workgroups per CU; each takes several slots in turn without letting the ring run empty.
 // =====================================================================================
 constexpr int ST_NW = 8, ST_NT = ST_NW * 64, ST_TPW = 16 / ST_NW, ST_NST = 5;
 constexpr int ST_KB = 32, ST_STAGE = ST_KB * ROWB;   // tokens and bytes (per tensor) of a stage
@@ -110,71 +112,107 @@ __global__ __launch_bounds__(ST_NT) void states_mfma_kernel(Geom g, const char* 
     char* sY = smem + ST_NST * ST_STAGE;   // ST_NST stages
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int s = blockIdx.x, grp = blockIdx.y;
-    int tok0, len;
-    slot_range(g, s, tok0, len);
-    const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
-
-    f32x16 acc[ST_TPW];
-#pragma unroll
-    for (int u = 0; u < ST_TPW; ++u)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
-
-    const int nblk = (len + ST_KB - 1) / ST_KB;
-    float l2 = DECAY ? decay_log2(g, grp) : 0.f;
-    asm volatile("" : "+v"(l2));   // first use here, not inside the loop (where the compiler's wait for it would drain the ring)
+    const int h = lane >> 5, l32 = lane & 31;
+    // A workgroup takes a run of consecutive slots u (u = group * T_s + slot), which is one
+    // contiguous stretch of each tensor, and keeps its ring full across their boundaries: the
+    // loads of the next slot's first blocks are on their way while the last blocks of this one
+    // are consumed.
+    const int total = g.T_s * g.G;
+    const int per_wg = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int u_first = (int)blockIdx.x * per_wg, nunits = min(total, u_first + per_wg);
+    struct Unit { int u, len, nblk; size_t row0; };
+    auto open_unit = [&](int u) {
+        Unit x;
+        x.u = u; x.len = 0; x.nblk = 0; x.row0 = 0;
+        if (u < nunits) {
+            int tok0;
+            slot_range(g, u % g.T_s, tok0, x.len);
+            x.nblk = (x.len + ST_KB - 1) / ST_KB;
+            x.row0 = ((size_t)(u / g.T_s) * g.N + tok0) * ROWB;
+        }
+        return x;
+    };
     // wave w fetches rows 4w .. 4w+3 of a stage: lane l the 16 bytes that land swizzled at its place
     const int myrow = 4 * w + (lane >> 4);
     const uint32_t dvo = dma_lane_off(w, lane);
-    auto issue = [&](int i, int slot) {
-        const int tok = i * ST_KB;
-        const size_t blk = row0 + (size_t)tok * ROWB;
+
+    Unit iu = open_unit(u_first);   // where the next load goes
+    int ib = 0, fill = 0, inflight = 0;     // its next block; ring slot to fill; stages issued and not yet consumed
+    auto issue_next = [&]() {
+        while (iu.u < nunits && ib >= iu.nblk) { iu = open_unit(iu.u + 1); ib = 0; }   // next slot with tokens
+        if (iu.u >= nunits) return;
+        const int tok = ib * ST_KB;
+        const size_t blk = iu.row0 + (size_t)tok * ROWB;
         // rows past the slot's end fetch its last row (always in bounds) and are zeroed after landing
-        const uint32_t voff = (uint32_t)(min(myrow, len - 1 - tok) * ROWB) + (dvo & (ROWB - 1));
-        dma16_nt(X + blk, voff, lds_addr_of(sX + slot * ST_STAGE + 4 * w * ROWB));
-        dma16_nt(Y + blk, voff, lds_addr_of(sY + slot * ST_STAGE + 4 * w * ROWB));
-    };
-    for (int i = 0; i < ST_NST - 1 && i < nblk; ++i) issue(i, i);
-
-    int slot = 0, fill = ST_NST - 1;   // slot of the block consumed now, and of the next block issued
-    for (int blk = 0; blk < nblk; ++blk) {
-        char* tx = sX + slot * ST_STAGE;
-        char* ty = sY + slot * ST_STAGE;
-        // this wave's loads of block blk have landed once at most the later blocks' are outstanding
-        const int later = min(nblk - 1 - blk, ST_NST - 2);
-        if (later >= 3) wait_vmcnt<3 * DPS>();
-        else if (later == 2) wait_vmcnt<2 * DPS>();
-        else if (later == 1) wait_vmcnt<DPS>();
-        else wait_vmcnt<0>();
-        const int tok = blk * ST_KB + myrow;
-        u32x4* px = reinterpret_cast<u32x4*>(tx + myrow * ROWB + (lane & 15) * 16);
-        if (tok >= len) {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            *px = z;
-            *reinterpret_cast<u32x4*>(ty + myrow * ROWB + (lane & 15) * 16) = z;
-        } else if (DECAY) {
-            // weight this wave's own rows of the X tile (a row takes one weight: the swizzle does not matter)
-            const float wt = exp2f((float)(anchor_start ? tok : len - 1 - tok) * l2);
-            *px = scale_bf16x8(*px, wt);
-        }
-        __syncthreads();   // block complete in LDS; every wave has left the block before it
-        if (blk + ST_NST - 1 < nblk) issue(blk + ST_NST - 1, fill);
-        update_tiles<ST_TPW, ST_KB>(acc, tx, ty, w * ST_TPW, lane);
-        slot = slot + 1 == ST_NST ? 0 : slot + 1;
+        const uint32_t voff = (uint32_t)(min(myrow, iu.len - 1 - tok) * ROWB) + (dvo & (ROWB - 1));
+        dma16_nt(X + blk, voff, lds_addr_of(sX + fill * ST_STAGE + 4 * w * ROWB));
+        dma16_nt(Y + blk, voff, lds_addr_of(sY + fill * ST_STAGE + 4 * w * ROWB));
         fill = fill + 1 == ST_NST ? 0 : fill + 1;
-    }
+        ++ib;
+        ++inflight;
+    };
+    for (int i = 0; i < ST_NST - 1; ++i) issue_next();
 
-    float* m = M + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
-    const int h = lane >> 5, l32 = lane & 31;
+    constexpr int NSTORE = 16 * ST_TPW;   // store instructions per wave that write a slot's state
+    int slot = 0, older_than_stores = 0;
+    for (Unit cu = open_unit(u_first); cu.u < nunits; cu = open_unit(cu.u + 1)) {
+        f32x16 acc[ST_TPW];
 #pragma unroll
-    for (int u = 0; u < ST_TPW; ++u) {
-        const int t = w * ST_TPW + u, a = t >> 2, b = t & 3;
+        for (int u = 0; u < ST_TPW; ++u)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = 32 * a + 8 * (v >> 2) + 4 * h + (v & 3);
-            m[row * D + 32 * b + l32] = acc[u][v];
+            for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
+        float l2 = DECAY ? decay_log2(g, cu.u / g.T_s) : 0.f;
+        asm volatile("" : "+v"(l2));   // waited for here, once per slot, not at its first use inside the block loop
+
+        for (int blk = 0; blk < cu.nblk; ++blk) {
+            char* tx = sX + slot * ST_STAGE;
+            char* ty = sY + slot * ST_STAGE;
+            // The oldest stage in flight has landed once at most the younger ones are outstanding.
+            // Memory operations retire in order and stores count too: the stages that were already
+            // on their way when the previous slot's state was stored are older than those NSTORE
+            // stores, which may therefore stay outstanding as well (waiting for them here would
+            // stop the stream at every slot boundary until the stores have been acknowledged).
+            if (older_than_stores > 0) {
+                --older_than_stores;
+                if (inflight >= 4) wait_vmcnt<3 * DPS + NSTORE>();
+                else if (inflight == 3) wait_vmcnt<2 * DPS + NSTORE>();
+                else if (inflight == 2) wait_vmcnt<DPS + NSTORE>();
+                else wait_vmcnt<NSTORE>();
+            } else {
+                if (inflight >= 4) wait_vmcnt<3 * DPS>();
+                else if (inflight == 3) wait_vmcnt<2 * DPS>();
+                else if (inflight == 2) wait_vmcnt<DPS>();
+                else wait_vmcnt<0>();
+            }
+            --inflight;
+            const int tok = blk * ST_KB + myrow;
+            u32x4* px = reinterpret_cast<u32x4*>(tx + myrow * ROWB + (lane & 15) * 16);
+            if (tok >= cu.len) {
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                *px = z;
+                *reinterpret_cast<u32x4*>(ty + myrow * ROWB + (lane & 15) * 16) = z;
+            } else if (DECAY) {
+                // weight this wave's own rows of the X tile (a row takes one weight: the swizzle does not matter)
+                const float wt = exp2f((float)(anchor_start ? tok : cu.len - 1 - tok) * l2);
+                *px = scale_bf16x8(*px, wt);
+            }
+            __syncthreads();   // block complete in LDS; every wave has left the block before it
+            issue_next();      // into the ring slot that block occupied
+            update_tiles<ST_TPW, ST_KB>(acc, tx, ty, w * ST_TPW, lane);
+            slot = slot + 1 == ST_NST ? 0 : slot + 1;
         }
+
+        float* m = M + (size_t)cu.u * (size_t)(D * D);
+#pragma unroll
+        for (int u = 0; u < ST_TPW; ++u) {
+            const int t = w * ST_TPW + u, a = t >> 2, b = t & 3;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 32 * a + 8 * (v >> 2) + 4 * h + (v & 3);
+                __builtin_nontemporal_store(acc[u][v], m + row * D + 32 * b + l32);
+            }
+        }
+        older_than_stores = inflight;
     }
 }
 
@@ -1038,7 +1076,14 @@ hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    dim3 grid(g.T_s, g.G), block(ST_NT);
+    // two workgroups per CU, each walking through its share of the slots
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    const long long nunits = (long long)g.T_s * g.G;
+    if (nunits == 0) return hipSuccess;
+    dim3 grid((unsigned)std::min<long long>(nunits, 2LL * cus)), block(ST_NT);
     hipLaunchKernelGGL(kern, grid, block, smem, st, g, static_cast<const char*>(K),
                        static_cast<const char*>(V), M, anchor_start);
     return hipGetLastError();

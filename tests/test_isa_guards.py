@@ -138,3 +138,20 @@ def test_softmax_kernels_keep_their_stage_loads_in_flight(isa_softmax):
             elif "vmcnt" in x and j > first_barrier:
                 assert in_asm, (name, j, x.strip())
     assert found == 3
+
+
+def test_states_kernel_store_count_matches_its_wait_arithmetic(isa):
+    """states_mfma_kernel lets the stores of a slot's state stay outstanding while it waits for
+    stage loads that are older than they are, by adding their number (16 per state tile held by a
+    wave, NSTORE in the source) to the counted wait.  Fewer store instructions than that in the
+    compiled code (merged stores) would make those waits too lenient."""
+    found = 0
+    for i, l in enumerate(isa):
+        if re.match(r"^_ZN.*states_mfma_kernelILb[01].*:", l):
+            found += 1
+            end = next(j for j in range(i, len(isa)) if isa[j].startswith(".Lfunc_end"))
+            body = isa[i:end]
+            stores = [x for x in body if re.search(r"\bglobal_store", x)]
+            assert len(stores) == 32 and all("global_store_dword " in x for x in stores), len(stores)
+            assert any("vmcnt(38)" in x for x in body) and any("vmcnt(6)" in x for x in body)
+    assert found == 2
