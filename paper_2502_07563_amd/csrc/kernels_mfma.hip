@@ -623,8 +623,8 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
                 for (int i = 0; i < 4; ++i) {
                     const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
                     const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
-                    if (rbase + row < len)
-                        *reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                    if (rbase + row < len)   // written once, read by a later kernel: non-temporal
+                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch));
                 }
             }
         }
@@ -912,7 +912,7 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
                     const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
                     const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
                     if (rbase + row < len)
-                        *reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch));
                 }
             }
         }
@@ -1048,7 +1048,7 @@ __global__ __launch_bounds__(RS_NW * 64) void rows_state_mfma_kernel(Geom g, Row
                 const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
                 if (rbase + row < len)
-                    *reinterpret_cast<u32x4*>(out + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch));
             }
         }
         if (it + 1 < nit) {
