@@ -1077,10 +1077,15 @@ hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     // two workgroups per CU, each walking through its share of the slots
+    static int cu_count[64] = {};   // per device ordinal, filled on first use (same value from any thread)
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+    if (dev >= 0) cus = cu_count[dev];
+    if (cus <= 0) {
+        if (dev < 0 || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        if (dev >= 0) cu_count[dev] = cus;
+    }
     const long long nunits = (long long)g.T_s * g.G;
     if (nunits == 0) return hipSuccess;
     dim3 grid((unsigned)std::min<long long>(nunits, 2LL * cus)), block(ST_NT);
