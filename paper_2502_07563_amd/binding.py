@@ -116,7 +116,41 @@ def _check(code, where):
 
 
 def _ptr(t):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+    """Device address of a tensor for the C ABI.  The kernels trust their pointers, so what torch
+    can tell about them is checked here: device memory, dense layout."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("lasp2: tensors must live in device memory (got a host tensor)")
+    if not t.is_contiguous():
+        raise ValueError("lasp2: tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _rows(p, t, n_tokens, name):
+    """A [B,H,n_tokens,d] tensor of the problem's dtype (None passes: the library reports it)."""
+    if t is None:
+        return
+    if t.dtype != p.torch_dtype:
+        raise ValueError(f"lasp2: {name} has dtype {t.dtype}, the problem is {p.torch_dtype}")
+    if t.numel() != p.B * p.H * n_tokens * p.d:
+        raise ValueError(f"lasp2: {name} has {t.numel()} elements, expected B*H*{n_tokens}*d = "
+                         f"{p.B * p.H * n_tokens * p.d}")
+
+
+def _f32(t, numel, name):
+    """An fp32 array of at least `numel` elements (states, log-sum-exp, scratch)."""
+    if t is None:
+        return
+    if t.dtype != torch.float32:
+        raise ValueError(f"lasp2: {name} must be float32, got {t.dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"lasp2: {name} has {t.numel()} elements, needs at least {numel}")
+
+
+def _states(p, t, name):
+    """An fp32 [B,H,T_s,d,d] state array."""
+    _f32(t, p.B * p.H * lasp2_num_slots(p) * p.d * p.d, name)
 
 
 def _stream(stream):
@@ -138,21 +172,29 @@ def lasp2_workspace_size(p: Problem) -> int:
 
 
 def lasp2_chunk_states(p: Problem, K, V, M, stream=None):
+    _rows(p, K, p.N, 'K'); _rows(p, V, p.N, 'V'); _states(p, M, 'M')
     _check(lib().lasp2_chunk_states(p.ref, _ptr(K), _ptr(V), _ptr(M), _stream(stream)),
            "lasp2_chunk_states")
 
 
 def lasp2_state_prefix(p: Problem, M, P, reverse=False, stream=None):
+    _states(p, M, 'M'); _states(p, P, 'P')
     _check(lib().lasp2_state_prefix(p.ref, _ptr(M), _ptr(P), 1 if reverse else 0, _stream(stream)),
            "lasp2_state_prefix")
 
 
 def lasp2_attn_fwd(p: Problem, Q, K, V, P, O, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('O', O)):
+        _rows(p, t, p.N, n)
+    _states(p, P, 'P')
     _check(lib().lasp2_attn_fwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(P), _ptr(O), _stream(stream)),
            "lasp2_attn_fwd")
 
 
 def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('dO', dO), ('dQ', dQ), ('dK', dK), ('dV', dV)):
+        _rows(p, t, p.N, n)
+    _states(p, P, 'P')
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lasp2_attn_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(P), _ptr(dQ),
                                 _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
@@ -160,14 +202,19 @@ def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=Non
 
 
 def lasp2_state_total(p: Problem, M, S, stream=None):
+    _states(p, M, 'M'); _states(p, S, 'S')
     _check(lib().lasp2_state_total(p.ref, _ptr(M), _ptr(S), _stream(stream)), "lasp2_state_total")
 
 
 def lasp2_nomask_fwd(p: Problem, Q, S, O, stream=None):
+    _rows(p, Q, p.N, 'Q'); _rows(p, O, p.N, 'O'); _states(p, S, 'S')
     _check(lib().lasp2_nomask_fwd(p.ref, _ptr(Q), _ptr(S), _ptr(O), _stream(stream)), "lasp2_nomask_fwd")
 
 
 def lasp2_nomask_bwd(p: Problem, Q, K, V, dO, S, dQ, dK, dV, workspace, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('dO', dO), ('dQ', dQ), ('dK', dK), ('dV', dV)):
+        _rows(p, t, p.N, n)
+    _states(p, S, 'S')
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lasp2_nomask_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(S), _ptr(dQ),
                                   _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
@@ -175,6 +222,9 @@ def lasp2_nomask_bwd(p: Problem, Q, K, V, dO, S, dQ, dK, dV, workspace, stream=N
 
 
 def lasp2_softmax_fwd(p: Problem, Q, K, V, O, LSE, causal=False, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('O', O)):
+        _rows(p, t, p.N, n)
+    _f32(LSE, p.B * p.H * p.N, 'LSE')
     _check(lib().lasp2_softmax_fwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE),
                                    1 if causal else 0, _stream(stream)), "lasp2_softmax_fwd")
 
@@ -186,6 +236,9 @@ def lasp2_softmax_workspace_size(p: Problem) -> int:
 
 
 def lasp2_softmax_bwd(p: Problem, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, causal=False, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('O', O), ('dO', dO), ('dQ', dQ), ('dK', dK), ('dV', dV)):
+        _rows(p, t, p.N, n)
+    _f32(LSE, p.B * p.H * p.N, 'LSE')
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lasp2_softmax_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
@@ -193,6 +246,8 @@ def lasp2_softmax_bwd(p: Problem, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, ca
 
 
 def lasp2_softmax_fwd_share(p: Problem, q_begin, q_len, Q_t, K, V, O_t, LSE_t, causal=False, stream=None):
+    _rows(p, Q_t, q_len, 'Q_t'); _rows(p, O_t, q_len, 'O_t'); _rows(p, K, p.N, 'K'); _rows(p, V, p.N, 'V')
+    _f32(LSE_t, p.B * p.H * q_len, 'LSE_t')
     _check(lib().lasp2_softmax_fwd_share(p.ref, ctypes.c_int64(q_begin), ctypes.c_int64(q_len), _ptr(Q_t),
                                          _ptr(K), _ptr(V), _ptr(O_t), _ptr(LSE_t), 1 if causal else 0,
                                          _stream(stream)), "lasp2_softmax_fwd_share")
@@ -207,6 +262,11 @@ def lasp2_softmax_share_workspace_size(p: Problem, q_len) -> int:
 
 def lasp2_softmax_bwd_share(p: Problem, q_begin, q_len, Q_t, K, V, O_t, dO_t, LSE_t, dQ_t, dK, dV, workspace,
                             causal=False, stream=None):
+    for n, t in (('Q_t', Q_t), ('O_t', O_t), ('dO_t', dO_t), ('dQ_t', dQ_t)):
+        _rows(p, t, q_len, n)
+    for n, t in (('K', K), ('V', V), ('dK', dK), ('dV', dV)):
+        _rows(p, t, p.N, n)
+    _f32(LSE_t, p.B * p.H * q_len, 'LSE_t')
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lasp2_softmax_bwd_share(p.ref, ctypes.c_int64(q_begin), ctypes.c_int64(q_len), _ptr(Q_t),
                                          _ptr(K), _ptr(V), _ptr(O_t), _ptr(dO_t), _ptr(LSE_t), _ptr(dQ_t),

@@ -177,3 +177,23 @@ def test_empty_problem_is_ok_without_pointers():
         assert lib.lasp2_nomask_bwd(r, *([None] * 9), ctypes.c_size_t(0), None) == 0
         assert lib.lasp2_softmax_fwd(r, *([None] * 5), 0, None) == 0
         assert lib.lasp2_softmax_bwd(r, *([None] * 10), ctypes.c_size_t(0), 0, None) == 0
+
+
+def test_binding_refuses_tensors_the_kernels_could_not_trust():
+    """The kernels trust their pointers; the Python binding checks what torch knows about a tensor
+    before handing its address over: device memory, dense layout, dtype, element count."""
+    import torch
+    p = B.Problem(1, 2, 128, 16, 64, 0, "f32", device="cpu")
+    t = torch.zeros((1, 2, 128, 16), dtype=torch.float32)
+    with pytest.raises(ValueError, match="device memory"):
+        B._ptr(t)
+    with pytest.raises(ValueError, match="dtype"):
+        B._rows(p, t.to(torch.bfloat16), 128, "Q")
+    with pytest.raises(ValueError, match="elements"):
+        B._rows(p, t[:, :, :64], 128, "Q")
+    with pytest.raises(ValueError, match="float32"):
+        B._f32(t.to(torch.float64), 10, "LSE")
+    with pytest.raises(ValueError, match="at least"):
+        B._f32(t.flatten()[:5], 10, "LSE")
+    B._rows(p, None, 128, "Q")      # a missing tensor is the library's to report (LASP2_ERR_NULL)
+    B._rows(p, t, 128, "Q")
