@@ -412,6 +412,12 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     // round-robin placement) get blocks s and 7-s, so that their triangular work adds up evenly.
     const int rb = (NW == 8) ? (w < 4 ? w : 11 - w) : w;
     const int t0 = w * TPW;
+    // With 256 rows per chunk the masked products are taken over the chunk's two 128-row halves
+    // separately (half hc of the rows against the same half of the keys only), and the half that
+    // lies further along the walk reads a second state snapshot taken between the halves: the
+    // same sum, with 44 % fewer score tiles than one 256-row triangle.
+    constexpr bool SPLIT = (C == 256);
+    const int hc = SPLIT ? (rb >> 2) : 0;
 
     const int nch = (len + C - 1) / C;
     const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
@@ -456,7 +462,12 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     // rows past the slot's end fetch its last row (they only feed output rows that are not stored).
     u32x4 qv[8];
     auto issue_q = [&](int c) {
-        const int r = min(c * C + 32 * rb + l32, len - 1);
+        // lane % 32 again, in a form the compiler cannot hoist out of the chunk loop: with every
+        // register taken, a hoisted row index would be spilled, and its reload from scratch is a
+        // vector-memory load whose wait drains the ring
+        int lrow;
+        asm volatile("v_and_b32 %0, 31, %1" : "=v"(lrow) : "v"(tid));
+        const int r = min(c * C + 32 * rb + lrow, len - 1);
         const char* p = A + row0 + (size_t)r * ROWB + 16 * h;
         gload16_async<0>(qv[0], p);
         gload16_async<32>(qv[1], p);
@@ -510,7 +521,16 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
             if (bi + 2 < NB) issue(bi + 2);
 
-            if (!anti && jb == 0) inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            if (!anti && jb == 0 && hc == 0) inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            if (SPLIT && jb == 2) {
+                // Between the halves: every wave has finished block 1 (this block's barrier) and read
+                // the previous snapshot long ago.  Causal: rows 128.. start from the state that
+                // includes the first half's keys.  Anti-causal: rows ..127 have now seen all keys of
+                // their half, and the accumulators hold minus the suffix beyond it.
+                write_snapshot<TPW>(sM, Macc, t0, l32, h, anti != 0);
+                __syncthreads();
+                if (hc == (anti ? 0 : 1)) inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            }
 
             // Operand fetches are issued a batch ahead of the MFMAs that consume them (two
             // small register buffers); sched_barrier keeps the compiler from sinking the
@@ -519,7 +539,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int kt = 2 * jb + half;      // 32-key tile index inside the chunk
-                const bool active = anti ? (kt >= rb) : (kt <= rb);
+                const bool active = (anti ? (kt >= rb) : (kt <= rb)) && (!SPLIT || (kt >> 2) == hc);
                 if (!active) continue;
                 // scores^T (keys x queries) = Bk_tile A_w^T ; the Cv operands of the second
                 // product are fetched while the first one runs
@@ -572,7 +592,8 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             // causal: the rows of the next chunk replace qf while the state update and the
             // store run (anti-causal still needs qf for the inter product at the chunk's end)
             if (!anti && jb + 1 == nblk && !last_chunk) issue_q(c + 1);
-            if (anti || !last_chunk) {
+            // (the causal walk's last chunk needs the update only for the snapshot between its halves)
+            if (anti || !last_chunk || (SPLIT && jb < 2 && nblk > 2)) {
                 // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
                 rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
                 SCHED_FENCE();
@@ -595,10 +616,13 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
         if (anti) {
             // every wave read the previous snapshot before its previous store, and at least one
-            // block barrier has passed since
+            // block barrier has passed since (with three blocks the snapshot between the halves was
+            // read inside the last block: one more barrier)
+            if (SPLIT && nblk == 3) __syncthreads();
             write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
             __syncthreads();
-            inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            // rows of the second half; of the first half too when the chunk ends inside it
+            if (!SPLIT || hc == 1 || nblk <= 2) inter_product<NOP>(Oacc, sM, qf, lo.nat);
             if (!last_chunk) issue_q(c + 1);
         }
 
