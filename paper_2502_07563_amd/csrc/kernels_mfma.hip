@@ -688,26 +688,69 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
 
 // =====================================================================================
 // Fused attention pass with scalar decay: out_i = sum_j lam^|i-j| (a_i . bk_j) cv_j over the
-// allowed pairs plus the decayed inter-chunk term.  Same tiles, stages and layouts as
-// attn_mfma_kernel<128> (four waves), with these differences:
+// allowed pairs plus the decayed inter-chunk term.  Same tiles, stages, layouts, wave placement
+// and asynchronous fetches as attn_mfma_kernel<C> (256 rows with eight waves, or 128 with four),
+// with these differences:
 //   - Anti-causal problems walk the slot BACKWARDS (blocks and chunks in descending order, the
 //     slot state being the exclusive suffix): with decay the forward walk with a subtracted
 //     suffix would have to divide by lam at every step.  Both directions therefore take the
-//     state snapshot and the inter-chunk product at the start of a chunk.
+//     state snapshot and the inter-chunk product when the walk enters a chunk, and, with 256
+//     rows, a second time when it enters the chunk's other 128-row half.
 //   - Each wave multiplies the rows of the Bk tile it staged by the token's weight as seen from
 //     the block's last token (causal, lam^(63-b)) or first token (anti-causal, lam^b) before the
 //     block barrier.  The state update then is lam^64 * state + Bk~^T Cv, and a score computed
 //     from the weighted rows needs only a factor per query, lam^(i - block start - 63) resp.
-//     lam^(block start - i), to become lam^|i-j| (a_i . bk_j); the exponents stay within +-63.
-//   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the chunk)
-//     or lam^(chunk length - a) (anti-causal).
-// The rows of A are fetched with ordinary loads here; this kernel is not tuned like the
-// undecayed one.
+//     lam^(block start - i), to become lam^|i-j| (a_i . bk_j); a query and the keys it meets lie
+//     in the same 128-row half, so the exponents stay within -63..64.
+//   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the half)
+//     or lam^(end of the half - a) (anti-causal).
 // =====================================================================================
-__global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
-                                                              AttnProblem p2, int nprob)
+// A value that is the same in every lane, moved to a scalar register (the builtin takes integers).
+__device__ __forceinline__ float uniform_f32(float x)
 {
-    constexpr int C = 128, NW = 4, TPW = 4, BPC = C / KB, IPW = 16 / NW, DPS = 2 * IPW, NOP = 8;
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
+}
+
+// Stores a wave's 32 output rows from the transposed accumulators (lane = row, four consecutive
+// d_v per register group) through its private 4 KiB LDS patch, half of d_v at a time, so that
+// every lane stores 16 contiguous bytes; rows at or beyond nrows are left out.  All lane-derived
+// addresses are rebuilt here from an index the compiler cannot hoist out of the caller's loops:
+// hoisted, they would be live across the whole walk and spilled.
+__device__ __forceinline__ void store_out_rows(const f32x16 (&Oacc)[4], char* stg, char* out_rows, int nrows, int tid)
+{
+    int ln;
+    asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+    const int l32 = ln & 31, h = ln >> 5, row = ln >> 3, ch = ln & 7;
+    char* wr = stg + l32 * 128 + 8 * h;
+    const int sw = l32 & 7;
+    const char* rd = stg + row * 128 + ((ch ^ (row & 7)) << 4);
+    char* gp = out_rows + (size_t)row * ROWB + 16 * ch;
+#pragma unroll
+    for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+        for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& o = Oacc[2 * hv + tvv];
+                u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                *reinterpret_cast<u32x2*>(wr + (((4 * tvv + q) ^ sw) << 4)) = pk;
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(rd + 1024 * i);
+            if (row + 8 * i < nrows)   // written once, read by a later kernel: non-temporal
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gp + (size_t)(8 * i) * ROWB + 128 * hv));
+        }
+    }
+}
+
+template <int C>
+__global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
+                                                                AttnProblem p2, int nprob)
+{
+    constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB, IPW = 16 / NW, DPS = 2 * IPW;
+    constexpr int NOP = (TPW + 1 > 4) ? 8 : 4;
+    constexpr bool SPLIT = (C == 256);
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* sK = smem;                              // Bk stages
     char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
@@ -731,8 +774,10 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
     slot_range(g, s, tok0, len);
     if (len <= 0) return;
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
-    const float l2 = decay_log2(g, grp);
-    const int rb = w, t0 = w * TPW;
+    const float l2 = uniform_f32(decay_log2(g, grp));   // one value per workgroup: scalar
+    const int rb = (NW == 8) ? (w < 4 ? w : 11 - w) : w;   // as in attn_mfma_kernel
+    const int hc = SPLIT ? (rb >> 2) : 0;                  // the 128-row half this wave's rows lie in
+    const int t0 = w * TPW;
 
     const int nch = (len + C - 1) / C;
     const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
@@ -773,28 +818,35 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
     LaneOffs<TPW> lo;
     make_lane_offs<TPW>(lo, lane, t0);
 
-    // weights of the Bk rows this wave stages (row b of the block), and lam^64 for the state
-    float wrow[IPW];
-#pragma unroll
-    for (int u = 0; u < IPW; ++u) {
-        const int b = 4 * (w * IPW + u) + (lane >> 4);
-        wrow[u] = exp2f((float)(rev ? b : KB - 1 - b) * l2);
-    }
-    const float wblk = exp2f((float)KB * l2);
+    // lam^64 for the state (the same in every lane)
+    const float wblk = uniform_f32(exp2f((float)KB * l2));
 
-    bf16x8 qf[8];   // this wave's 32 rows of A as B-operand fragments (column = row of A, k = d)
-    auto load_q = [&](int cc) {
-        const int r = cc * C + 32 * rb + l32;
-        const bool ok = r < len;
+    // This wave's 32 rows of A as B-operand fragments, fetched asynchronously as in
+    // attn_mfma_kernel; rows past the slot's end fetch its last row (they only feed output rows
+    // that are not stored, and a column of the products depends on its own row alone).
+    u32x4 qv[8];
+    auto issue_q = [&](int cc) {
+        int lrow;   // lane % 32 again, in a form the compiler cannot hoist (and then spill)
+        asm volatile("v_and_b32 %0, 31, %1" : "=v"(lrow) : "v"(tid));
+        const int r = min(cc * C + 32 * rb + lrow, len - 1);
         const char* p = A + row0 + (size_t)r * ROWB + 16 * h;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            u32x4 z = {0u, 0u, 0u, 0u};
-            u32x4 x = ok ? *reinterpret_cast<const u32x4*>(p + 32 * ks) : z;
-            qf[ks] = __builtin_bit_cast(bf16x8, x);
-        }
+        gload16_async<0>(qv[0], p);
+        gload16_async<32>(qv[1], p);
+        gload16_async<64>(qv[2], p);
+        gload16_async<96>(qv[3], p);
+        gload16_async<128>(qv[4], p);
+        gload16_async<160>(qv[5], p);
+        gload16_async<192>(qv[6], p);
+        gload16_async<224>(qv[7], p);
     };
-    load_q(rev ? nch - 1 : 0);
+    auto take_q = [&](uint32_t zero) {
+        const u32x4 z = {zero, zero, zero, zero};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qv[ks] = qv[ks] | z;
+    };
+    issue_q(rev ? nch - 1 : 0);
+    take_q(wait_vmcnt_token<0>());
+    const bf16x8 (&qf)[8] = reinterpret_cast<const bf16x8 (&)[8]>(qv);
 
     int bi = 0;          // walk position of the block being consumed
     int prev_nblk = BPC;
@@ -805,8 +857,10 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
         const int clen = min(C, len - cc * C);
         const bool last_chunk = (c + 1 == nch);
 
-        // The previous chunk read the snapshot in its first block; one of its later block
-        // barriers separates that from this write unless it had a single block.
+        // The previous chunk read its last snapshot in its first or third block; one of its later
+        // block barriers separates that from this write unless it had a single block (a chunk of
+        // three blocks is the slot's last one: nothing follows it in the forward walk, and the
+        // backward walk enters its lower half at the second block).
         if (prev_nblk < 2) __syncthreads();
         write_snapshot<TPW>(sM, Macc, t0, l32, h, false);
 
@@ -821,22 +875,44 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
             const int jbb = bb - b_lo;                         // its index inside the chunk
             char* tK = sK + (bi % NSTAGE) * STAGE_BYTES;
             char* tV = sV + (bi % NSTAGE) * STAGE_BYTES;
-            if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            // this wave's loads of block bi have landed (those of bi+1 may still fly); in the first
+            // two blocks after a chunk boundary the previous chunk's eight stores are younger too
+            if (c > 0 && jb < 2) {
+                if (bi + 1 < NB) wait_vmcnt<DPS + 8>(); else wait_vmcnt<8>();
+            } else {
+                if (bi + 1 < NB) wait_vmcnt<DPS>(); else wait_vmcnt<0>();
+            }
             if (bb * KB + KB > len) zero_tail_rows<NW>(bb * KB, len, tK, tV, w, lane);
             // weight this wave's own rows of the Bk tile (a whole row takes one weight, so the
             // swizzle does not matter here)
 #pragma unroll
             for (int u = 0; u < IPW; ++u) {
-                u32x4* pk = reinterpret_cast<u32x4*>(tK + (4 * (w * IPW + u) + (lane >> 4)) * ROWB + (lane & 15) * 16);
-                *pk = scale_bf16x8(*pk, wrow[u]);
+                const int b = 4 * (w * IPW + u) + (lane >> 4);
+                const float wr = __builtin_amdgcn_exp2f((float)(rev ? b : KB - 1 - b) * l2);
+                u32x4* pk = reinterpret_cast<u32x4*>(tK + b * ROWB + (lane & 15) * 16);
+                *pk = scale_bf16x8(*pk, wr);
             }
             __syncthreads();   // block complete and weighted in LDS; every wave is past the previous one
             if (bi + 2 < NB) issue(bi + 2);
 
-            if (jb == 0) {
+            // The walk enters a half of the chunk (its first block, or with 256 rows the first block of
+            // the other half): the rows of that half take the inter-chunk product from the state as it
+            // stands, which sits one token before the half (causal) or one after it (anti-causal).
+            const int hb = SPLIT ? (jbb >> 1) : 0;
+            const bool mid = SPLIT && jb > 0 && jbb == (rev ? 1 : 2);
+            if (mid) {
+                // every wave has passed this block's barrier, so the reads of the chunk's first
+                // snapshot (in its first block) are over
+                write_snapshot<TPW>(sM, Macc, t0, l32, h, false);
+                __syncthreads();
+            }
+            if ((jb == 0 || mid) && hc == hb) {
                 inter_product<NOP>(Oacc, sM, qf, lo.nat);
-                // the state sits one token before the chunk (causal) or one after it (anti-causal)
-                const float wq = exp2f((float)(rev ? clen - (32 * rb + l32) : 32 * rb + l32 + 1) * l2);
+                int lrow;   // lane % 32, kept out of the loop-invariant (and then spilled) values
+                asm volatile("v_and_b32 %0, 31, %1" : "=v"(lrow) : "v"(tid));
+                const int a = 32 * rb + lrow;
+                const int e = rev ? max(min(clen, 128 * (hb + 1)) - a, 0) : a - 128 * hb + 1;
+                const float wq = __builtin_amdgcn_exp2f((float)e * l2);
 #pragma unroll
                 for (int tv = 0; tv < 4; ++tv)
 #pragma unroll
@@ -847,7 +923,7 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int kt = 2 * jbb + half;      // 32-key tile index inside the chunk
-                const bool active = rev ? (kt >= rb) : (kt <= rb);
+                const bool active = (rev ? (kt >= rb) : (kt <= rb)) && (!SPLIT || (kt >> 2) == hc);
                 if (!active) continue;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks]);
@@ -874,7 +950,7 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
                 {
                     // from the row weights of the block to lam^|i-j|: one factor per query
                     const int qi = 32 * rb + l32 - KB * jbb;   // query index relative to the block's start
-                    const float f = exp2f((float)(rev ? -qi : qi - (KB - 1)) * l2);
+                    const float f = __builtin_amdgcn_exp2f((float)(rev ? -qi : qi - (KB - 1)) * l2);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = 8 * (v >> 2) + 4 * h + (v & 3);
@@ -897,48 +973,47 @@ __global__ __launch_bounds__(256) void attn_decay_mfma_kernel(Geom g, AttnProble
                 SCHED_FENCE();
             }
 
-            if (!last_chunk) {
+            // the rows of the next chunk replace qf while the state update and the store run
+            if (jb + 1 == nblk && !last_chunk) issue_q(rev ? cc - 1 : cc + 1);
+            // (the walk's last chunk needs the update only for the snapshot between its halves)
+            if (!last_chunk || (SPLIT && (rev ? jbb >= 2 : (jbb < 2 && nblk > 2)))) {
                 // running state = lam^n * state + (weighted Bk block)^T Cv block, n = the block's
                 // tokens (fewer than 64 only in the slot's last block, which the backward walk
                 // meets first)
-                const float wb = (bb * KB + KB <= len) ? wblk : exp2f((float)(len - bb * KB) * l2);
+                const float wb = (bb * KB + KB <= len) ? wblk : __builtin_amdgcn_exp2f((float)(len - bb * KB) * l2);
 #pragma unroll
                 for (int u = 0; u < TPW; ++u)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) Macc[u][v] *= wb;
-#pragma unroll
-                for (int ks = 0; ks < KB / 16; ++ks) {
-                    rd_update<TPW, NOP>(bufA, tK, tV, ks, lo);
-                    SCHED_FENCE();
-                    mm_update<TPW, NOP>(Macc, bufA);
-                    SCHED_FENCE();
-                }
+                rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufB, tK, tV, 1, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufA);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufA, tK, tV, 2, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufB);
+                SCHED_FENCE();
+                rd_update<TPW, NOP>(bufB, tK, tV, 3, lo);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufA);
+                SCHED_FENCE();
+                mm_update<TPW, NOP>(Macc, bufB);
             }
         }
         prev_nblk = nblk;
-        if (!last_chunk) load_q(rev ? cc - 1 : cc + 1);
 
+        // store this wave's 32 output rows, as in attn_mfma_kernel
         {
-            char* stg = sO + w * 4096;
             const int rbase = cc * C + 32 * rb;
-#pragma unroll
-            for (int hv = 0; hv < 2; ++hv) {
-#pragma unroll
-                for (int tvv = 0; tvv < 2; ++tvv)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x16& o = Oacc[2 * hv + tvv];
-                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
-                        *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
-                    }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
-                    if (rbase + row < len)
-                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch));
-                }
-            }
+            store_out_rows(Oacc, sO + w * 4096, out + row0 + (size_t)rbase * ROWB, len - rbase, tid);
+        }
+        // Only the eight stores above were issued after the rows of A for the next chunk.  All eight
+        // execute when the chunk is full; the backward walk starts with the slot's last chunk, which
+        // may not be.
+        if (!last_chunk) {
+            if (clen == C) take_q(wait_vmcnt_token<8>()); else take_q(wait_vmcnt_token<0>());
         }
     }
 }
@@ -1119,18 +1194,27 @@ hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float
 }
 
 namespace {
-hipError_t launch_attn_decay(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
-                             const AttnProblem& p2, int nprob, hipStream_t st)
+template <int C>
+hipError_t launch_attn_decay_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
+                               const AttnProblem& p2, int nprob, hipStream_t st)
 {
-    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 4 * 4096;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decay_mfma_kernel),
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + (C / 32) * 4096;
+    auto kern = attn_decay_mfma_kernel<C>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
-    dim3 grid(gx), block(256);
-    hipLaunchKernelGGL(attn_decay_mfma_kernel, grid, block, smem, st, g, p0, p1, p2, nprob);
+    dim3 grid(gx), block(C * 2);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, p2, nprob);
     return hipGetLastError();
+}
+
+hipError_t launch_attn_decay(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
+                             const AttnProblem& p2, int nprob, hipStream_t st)
+{
+    if (wide_chunks(g)) return launch_attn_decay_C<256>(g, p0, p1, p2, nprob, st);
+    return launch_attn_decay_C<128>(g, p0, p1, p2, nprob, st);
 }
 }  // namespace
 

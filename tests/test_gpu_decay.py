@@ -73,7 +73,11 @@ def test_fp32_shapes(oracle, N, d, C, L):
 
 @pytest.mark.parametrize("N,d,C,L", [(1024, 128, 256, 512), (900, 64, 128, 256), (300, 128, 64, 0),
                                      (2304, 128, 256, 1024), (1900, 128, 256, 512), (200, 128, 256, 0),
-                                     (777, 128, 50, 150), (67, 128, 1, 3)])
+                                     (777, 128, 50, 150), (67, 128, 1, 3),
+                                     # last slot = one full 256-row chunk + 150 tokens (three blocks, ends
+                                     # inside the second half) / + 40 tokens (a single ragged block): the
+                                     # backward walk starts with that chunk
+                                     (2454, 128, 256, 1024), (2344, 128, 256, 1024)])
 def test_bf16_shapes(oracle, N, d, C, L):
     _run(oracle, 1, 3, N, d, C, L, "bf16", seed=110 + N)
 
@@ -83,7 +87,7 @@ def test_bf16_d128_strong_decay_takes_the_plain_kernels(oracle):
     _run(oracle, 1, 3, 700, 128, 128, 256, "bf16", seed=115, lam=[0.2, 0.99, 0.05])
 
 
-@pytest.mark.parametrize("dtype,d,C,L", [("f32", 32, 64, 128), ("bf16", 128, 128, 256)])
+@pytest.mark.parametrize("dtype,d,C,L", [("f32", 32, 64, 128), ("bf16", 128, 128, 256), ("bf16", 128, 256, 1024)])
 def test_packed_documents(oracle, dtype, d, C, L):
     cu = synth.doc_offsets(6, 1536, 7, mean_len=1536 / 7, min_len=1)
     _run(oracle, 1, 3, 1536, d, C, L, dtype, seed=120, cu=cu)

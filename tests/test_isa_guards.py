@@ -97,6 +97,36 @@ def test_no_compiler_placed_vmcnt_wait_in_the_walk(isa):
                 assert in_asm, (cname, i, l.strip())
 
 
+def test_decay_attention_kernels_keep_their_loads_in_flight(isa):
+    """The decayed pass counts its stage loads and the loads of the next chunk's rows by hand like
+    the undecayed one: no scratch memory, and after the first barrier no vmcnt wait outside the
+    kernel's own asm blocks."""
+    text = "\n".join(isa)
+    found = 0
+    for i, l in enumerate(isa):
+        m = re.match(r"^(_ZN.*attn_decay_mfma_kernelILi(\d+).*):", l)
+        if not m:
+            continue
+        found += 1
+        sym, cname = m.group(1), m.group(2)
+        end = next(j for j in range(i, len(isa)) if "s_endpgm" in isa[j])
+        body = isa[i:end]
+        assert not any("scratch_" in x for x in body), f"attn_decay_mfma_kernel<{cname}> touches scratch memory"
+        k = re.search(r"\.amdhsa_kernel " + re.escape(sym) + r".*?\.amdhsa_private_segment_fixed_size (\d+)",
+                      text, flags=re.S)
+        assert k and int(k.group(1)) == 0, f"attn_decay_mfma_kernel<{cname}> has a private segment"
+        first_barrier = next(j for j, x in enumerate(body) if "s_barrier" in x)
+        in_asm = False
+        for j, x in enumerate(body):
+            if "#ASMSTART" in x:
+                in_asm = True
+            elif "#ASMEND" in x:
+                in_asm = False
+            elif "vmcnt" in x and j > first_barrier:
+                assert in_asm, (cname, j, x.strip())
+    assert found == 2
+
+
 @pytest.fixture(scope="module")
 def isa_softmax(tmp_path_factory):
     from paper_2502_07563_amd import build as b
