@@ -358,6 +358,45 @@ __device__ __forceinline__ void inter_product(f32x16 (&Oacc)[4], const char* sM,
     }
 }
 
+// A value that is the same in every lane, moved to a scalar register (the builtin takes integers).
+__device__ __forceinline__ float uniform_f32(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
+}
+
+// Stores a wave's 32 output rows from the transposed accumulators (lane = row, four consecutive
+// d_v per register group) through its private 4 KiB LDS patch, half of d_v at a time, so that
+// every lane stores 16 contiguous bytes; rows at or beyond nrows are left out.  All lane-derived
+// addresses are rebuilt here from an index the compiler cannot hoist out of the caller's loops:
+// hoisted, they would be live across the whole walk and spilled.
+__device__ __forceinline__ void store_out_rows(const f32x16 (&Oacc)[4], char* stg, char* out_rows, int nrows, int tid)
+{
+    int ln;
+    asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+    const int l32 = ln & 31, h = ln >> 5, row = ln >> 3, ch = ln & 7;
+    char* wr = stg + l32 * 128 + 8 * h;
+    const int sw = l32 & 7;
+    const char* rd = stg + row * 128 + ((ch ^ (row & 7)) << 4);
+    char* gp = out_rows + (size_t)row * ROWB + 16 * ch;
+#pragma unroll
+    for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+        for (int tvv = 0; tvv < 2; ++tvv)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& o = Oacc[2 * hv + tvv];
+                u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
+                *reinterpret_cast<u32x2*>(wr + (((4 * tvv + q) ^ sw) << 4)) = pk;
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(rd + 1024 * i);
+            if (row + 8 * i < nrows)   // written once, read by a later kernel: non-temporal
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gp + (size_t)(8 * i) * ROWB + 128 * hv));
+        }
+    }
+}
+
 // The grid is one-dimensional and carries nprob problems that walk the same slots.  The
 // (group, slot) pairs are numbered unit = group * T_s + slot, and workgroup x handles unit
 // 8*(x/(8 nprob)) + x%8 of problem (x/8)%nprob.  With workgroups dealt to the eight XCDs
@@ -626,31 +665,10 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             if (!last_chunk) issue_q(c + 1);
         }
 
-        // Store this wave's 32 output rows.  The accumulators hold out^T (lane = row, four
-        // consecutive d_v per register group); they are transposed through a wave-private
-        // 4 KiB LDS patch, half of d_v at a time, so that every lane stores 16 contiguous bytes
-        // and a wave instruction covers whole 128-byte line halves.
+        // store this wave's 32 output rows
         {
-            char* stg = sO + w * 4096;
             const int rbase = c * C + 32 * rb;
-#pragma unroll
-            for (int hv = 0; hv < 2; ++hv) {
-#pragma unroll
-                for (int tvv = 0; tvv < 2; ++tvv)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x16& o = Oacc[2 * hv + tvv];
-                        u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
-                        *reinterpret_cast<u32x2*>(stg + l32 * 128 + (((4 * tvv + q) ^ (l32 & 7)) << 4) + 8 * h) = pk;
-                    }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int idx = lane + 64 * i, row = idx >> 3, ch = idx & 7;
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + row * 128 + ((ch ^ (row & 7)) << 4));
-                    if (rbase + row < len)   // written once, read by a later kernel: non-temporal
-                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + row0 + (size_t)(rbase + row) * ROWB + 128 * hv + 16 * ch));
-                }
-            }
+            store_out_rows(Oacc, sO + w * 4096, out + row0 + (size_t)rbase * ROWB, len - rbase, tid);
         }
         // Only the eight stores above were issued after the rows of A for the next chunk (they
         // all execute: a chunk that is not the last is full).
@@ -705,45 +723,6 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
 //   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the half)
 //     or lam^(end of the half - a) (anti-causal).
 // =====================================================================================
-// A value that is the same in every lane, moved to a scalar register (the builtin takes integers).
-__device__ __forceinline__ float uniform_f32(float x)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
-}
-
-// Stores a wave's 32 output rows from the transposed accumulators (lane = row, four consecutive
-// d_v per register group) through its private 4 KiB LDS patch, half of d_v at a time, so that
-// every lane stores 16 contiguous bytes; rows at or beyond nrows are left out.  All lane-derived
-// addresses are rebuilt here from an index the compiler cannot hoist out of the caller's loops:
-// hoisted, they would be live across the whole walk and spilled.
-__device__ __forceinline__ void store_out_rows(const f32x16 (&Oacc)[4], char* stg, char* out_rows, int nrows, int tid)
-{
-    int ln;
-    asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
-    const int l32 = ln & 31, h = ln >> 5, row = ln >> 3, ch = ln & 7;
-    char* wr = stg + l32 * 128 + 8 * h;
-    const int sw = l32 & 7;
-    const char* rd = stg + row * 128 + ((ch ^ (row & 7)) << 4);
-    char* gp = out_rows + (size_t)row * ROWB + 16 * ch;
-#pragma unroll
-    for (int hv = 0; hv < 2; ++hv) {
-#pragma unroll
-        for (int tvv = 0; tvv < 2; ++tvv)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x16& o = Oacc[2 * hv + tvv];
-                u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
-                *reinterpret_cast<u32x2*>(wr + (((4 * tvv + q) ^ sw) << 4)) = pk;
-            }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(rd + 1024 * i);
-            if (row + 8 * i < nrows)   // written once, read by a later kernel: non-temporal
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gp + (size_t)(8 * i) * ROWB + 128 * hv));
-        }
-    }
-}
-
 template <int C>
 __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
                                                                 AttnProblem p2, int nprob)
