@@ -676,6 +676,435 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     }
 }
 
+// Counted waits with a run-time count.  A wave keeps the number of vector-memory instructions it
+// has certainly issued (stage loads, row loads, full output stores; a store that may be skipped
+// is left out, which only makes a wait stricter) and, for each batch of loads it will wait for,
+// that number right after the batch.  The difference is how many younger instructions may still
+// be outstanding when the batch is needed; memory instructions retire in order.  All batches here
+// are multiples of four instructions.
+__device__ __forceinline__ void wait_vmcnt_le(int n)
+{
+    if (n >= 24) wait_vmcnt<24>();
+    else if (n >= 20) wait_vmcnt<20>();
+    else if (n >= 16) wait_vmcnt<16>();
+    else if (n >= 12) wait_vmcnt<12>();
+    else if (n >= 8) wait_vmcnt<8>();
+    else if (n >= 4) wait_vmcnt<4>();
+    else wait_vmcnt<0>();
+}
+
+__device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
+{
+    if (n >= 24) return wait_vmcnt_token<24>();
+    if (n >= 20) return wait_vmcnt_token<20>();
+    if (n >= 16) return wait_vmcnt_token<16>();
+    if (n >= 12) return wait_vmcnt_token<12>();
+    if (n >= 8) return wait_vmcnt_token<8>();
+    if (n >= 4) return wait_vmcnt_token<4>();
+    return wait_vmcnt_token<0>();
+}
+
+// The fused pass with 256-row chunks, the work of the two 128-row halves skewed against each
+// other.  Same problems, grid, tiles, stages and walk as attn_mfma_kernel<256>; the difference is
+// when a wave finishes its rows.  A 64-token block concerns the rows of one half only, so at any
+// time the four waves of the other half have nothing but their share of the state update to do.
+// Here they use that time for what attn_mfma_kernel does with all eight waves at the end of a
+// chunk:
+//   - rows of the first half are complete once block 1 has been consumed (anti-causal: once the
+//     state between the halves has been applied, at block 2): their waves fetch the next chunk's
+//     rows and store during blocks 2 and 3, while the second half's waves compute;
+//   - rows of the second half are complete at the end of the chunk (anti-causal: once the state
+//     at the chunk's end has been applied): their waves keep the accumulators, and finish and
+//     store during block 0 of the next chunk, while the first half's waves compute.  The
+//     snapshot taken at the top of a chunk is therefore the state the previous chunk's second
+//     half still needs (anti-causal) as well as the one this chunk's first half starts from
+//     (causal), and needs no barrier of its own: block 0's barrier publishes it.
+// The two halves' waves and the two directions run separate copies of the walk (HC1, ANTI), each
+// a straight line through the four blocks of a chunk, so that the accumulators and the rows in
+// flight have one definition per place and are not copied at control-flow joins.  Every chunk is
+// walked as four blocks: a block that lies wholly past the slot's end is not loaded but zeroed, and
+// contributes nothing.  All copies pass the same barriers: one per block, one between the halves,
+// and for the anti-causal walk one at the end.  Each half stores at a different time, so the
+// waits are counted at run time (wait_vmcnt_le).
+template <bool HC1, bool ANTI>
+__device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, char* smem, int tid, int w,
+                                          int rb, int grp, int s, int tok0, int len)
+{
+    constexpr int C = 256, NW = 8, TPW = 2, BPC = 4, DPS = 4, NOP = 4;
+    char* sK = smem;                              // Bk stages
+    char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
+    char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
+    char* sO = sM + D * ROWB;                     // output staging, 4 KiB per wave
+    const int lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const char* __restrict__ A = pr.A;
+    const char* __restrict__ Bk = pr.Bk;
+    const char* __restrict__ Cv = pr.Cv;
+    char* __restrict__ out = pr.out;
+    const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
+    const int t0 = w * TPW;
+    const int nch = (len + C - 1) / C;
+
+    // Stage loads of block i.  The per-lane source offsets are rebuilt at every call from a lane index
+    // the compiler cannot hoist: kept across the walk they cost registers this kernel does not have.
+    auto issue = [&](int i) __attribute__((always_inline)) {
+        int ln;
+        asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+        uint32_t dvo[16 / NW];
+#pragma unroll
+        for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, ln);
+        dma_block<NW>(Bk, Cv, row0, i * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
+                      sV + (i % NSTAGE) * STAGE_BYTES, w, ln, dvo);
+    };
+    issue(0);
+    if (KB < len) issue(1);
+
+    // running state tiles, C/D layout: rows = d_k (first index), columns = d_v; negated for the
+    // anti-causal walk (see attn_mfma_kernel)
+    f32x16 Macc[TPW];
+    {
+        const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+        const float sg = ANTI ? -1.f : 1.f;
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+            const int t = t0 + u, a = t >> 2, b = t & 3;
+            if (!pr.transpose_state) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    Macc[u][v] = sg * st[(32 * a + 8 * (v >> 2) + 4 * h + (v & 3)) * D + 32 * b + l32];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 x = *reinterpret_cast<const f32x4*>(st + (32 * b + l32) * D + 32 * a + 8 * q + 4 * h);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Macc[u][4 * q + e] = sg * x[e];
+                }
+            }
+        }
+    }
+
+    // Per-lane byte offsets into a swizzled tile.  The swizzle is an XOR on the 16-byte chunk index
+    // (with bits of the row index), so the offsets of a family differ by an XOR with a constant and
+    // a multiple of the row size, and only one per family is kept in a register:
+    //   natural row l32, d step ks:                        nat0 ^ (ks << 5)
+    //   transposed fetch of columns 32 tv + l32, rows r:   pvA ^ (tv << 6);  rows r + 8: (.. ^ 32) + 8 rows
+    //   state update, X^T operand, rows r:                 uaA;              rows r + 4: (uaA ^ 16) + 4 rows
+    //   state update, Y operand of tile u:                 uaA ^ ydel ^ (u << 6), ydel the same in all lanes
+    //   snapshot piece q of tile u:                        (snp0 ^ (q << 4)) + u * 32 rows
+    // (a stage's base is a multiple of its 16 KiB, so base + offset can be formed first).
+    const int li = lane & 15, g2 = (lane >> 4) & 1, cl = 16 * g2 + 4 * (li & 3), rl = li >> 2;
+    const uint32_t nat0 = (uint32_t)tile_off(l32, h);
+    const uint32_t pvA = (uint32_t)tr_off(4 * h + rl, cl);
+    const uint32_t uaA = (uint32_t)tr_off(8 * h + rl, 32 * (t0 >> 2) + cl);
+    const uint32_t ydel = (uint32_t)(((t0 >> 2) ^ (t0 & 3)) << 6);
+    const uint32_t snp0 = lds_addr_of(sM) + (uint32_t)tile_off(32 * (t0 & 3) + l32, 4 * (t0 >> 2)) + 8 * h;
+
+    // this wave's 32 rows of A as B-operand fragments, fetched asynchronously (see attn_mfma_kernel);
+    // rows past the slot's end fetch its last row
+    u32x4 qv[8];
+    auto issue_q = [&](int c) __attribute__((always_inline)) {
+        int ln;   // the lane index again, in a form the compiler cannot hoist out of the loop (and spill)
+        asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+        const int r = min(c * C + 32 * rb + (ln & 31), len - 1);
+        const char* p = A + row0 + (size_t)r * ROWB + 16 * (ln >> 5);
+        gload16_async<0>(qv[0], p);
+        gload16_async<32>(qv[1], p);
+        gload16_async<64>(qv[2], p);
+        gload16_async<96>(qv[3], p);
+        gload16_async<128>(qv[4], p);
+        gload16_async<160>(qv[5], p);
+        gload16_async<192>(qv[6], p);
+        gload16_async<224>(qv[7], p);
+    };
+    auto take_q = [&](uint32_t zero) __attribute__((always_inline)) {
+        const u32x4 z = {zero, zero, zero, zero};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qv[ks] = qv[ks] | z;
+    };
+    // The first half's waves need the rows of chunk 0 at once; the second half's request theirs in
+    // block 0.  (A request whose registers are never read afterwards must not be made: the compiler
+    // would reuse those registers while the load is still on its way.)
+    if (!HC1) {
+        issue_q(0);
+        take_q(wait_vmcnt_token<0>());   // also completes blocks 0 and 1 and the state
+    } else {
+        wait_vmcnt<0>();
+    }
+    const bf16x8 (&qf)[8] = reinterpret_cast<const bf16x8 (&)[8]>(qv);
+
+    // snapshot of the running state, bf16 [d_v][d_k] (the anti-causal walk holds minus the state)
+    auto snapshot = [&]() __attribute__((always_inline)) {
+        const float sg = ANTI ? -1.f : 1.f;
+        uint32_t s0 = snp0;
+        pin_vgpr(s0);   // keeps the eight addresses from being formed once and held
+#pragma unroll
+        for (int u = 0; u < TPW; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32x2 pk = {pack2(sg * Macc[u][4 * q], sg * Macc[u][4 * q + 1]),
+                            pack2(sg * Macc[u][4 * q + 2], sg * Macc[u][4 * q + 3])};
+                *reinterpret_cast<__attribute__((address_space(3))) u32x2*>((s0 ^ (q << 4)) + u * (32 * ROWB)) = pk;
+            }
+    };
+
+    f32x16 Oacc[4];
+    auto zero_out = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+    };
+    // inter-chunk term: out^T += S^T A^T with S^T = snapshot; operands of d_k step ks+1 are
+    // fetched while the MFMAs of step ks run
+    auto inter = [&]() __attribute__((always_inline)) {
+        uint32_t n0 = nat0;
+        pin_vgpr(n0);   // the sum below is formed here, not once before the walk (and then spilled)
+        const uint32_t aM = lds_addr_of(sM) + n0;
+        bf16x8 bA[4], bB[4];
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv) bA[tv] = lds_read16_u(aM + tv * (32 * ROWB));
+        SCHED_FENCE();
+#pragma unroll
+        for (int ks = 0; ks < 8; ks += 2) {
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) bB[tv] = lds_read16_u((aM ^ ((ks + 1) << 5)) + tv * (32 * ROWB));
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bA[tv], qf[ks], Oacc[tv]);
+            SCHED_FENCE();
+            if (ks + 2 < 8) {
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) bA[tv] = lds_read16_u((aM ^ ((ks + 2) << 5)) + tv * (32 * ROWB));
+            }
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bB[tv], qf[ks + 1], Oacc[tv]);
+            SCHED_FENCE();
+        }
+    };
+
+    // vector-memory instructions certainly issued since the full wait above, and the marks of the
+    // batches to wait for
+    int issued = 0, seq_cur = 0, seq_next = 0, seq_q = 0;
+
+    // stores this wave's rows of chunk c (none when c < 0) and clears the accumulators
+    auto store_rows = [&](int c) __attribute__((always_inline)) {
+        const int rbase = c * C + 32 * rb;
+        const int nrows = c < 0 ? 0 : len - rbase;
+        store_out_rows(Oacc, sO + w * 4096, out + row0 + (ptrdiff_t)rbase * ROWB, nrows, tid);
+        if (nrows >= 32) issued += 8;   // all eight stores certainly execute
+        SCHED_FENCE();
+        zero_out();
+    };
+
+    char* tK = sK;
+    char* tV = sV;
+    // start of block bi: its loads have landed, the block is complete in LDS, every wave is past
+    // block bi - 1, and the loads of block bi + 2 are on their way
+    auto begin = [&](int bi) __attribute__((always_inline)) {
+        tK = sK + (bi % NSTAGE) * STAGE_BYTES;
+        tV = sV + (bi % NSTAGE) * STAGE_BYTES;
+        wait_vmcnt_le(issued - seq_cur);
+        if (bi * KB + KB > len) {   // at the slot's end only: keep these addresses out of the walk's registers
+            int ln;
+            asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+            zero_tail_rows<NW>(bi * KB, len, tK, tV, w, ln);
+        }
+        __syncthreads();
+        seq_cur = seq_next;
+        if ((bi + 2) * KB < len) { issue(bi + 2); issued += DPS; }
+        seq_next = issued;
+    };
+
+    // masked products of this wave's rows with the two 32-key tiles of block JB of the chunk
+    auto tiles = [&](auto jb_c) __attribute__((always_inline)) {
+        constexpr int JB = decltype(jb_c)::value;
+        // per-lane addresses into this block's stage, opaque to the compiler: it would otherwise fold
+        // the constants of every use into copies that it keeps (and spills) across the whole walk
+        uint32_t aK = lds_addr_of(tK) + nat0, aVA = lds_addr_of(tV) + pvA;
+        pin_vgpr(aK); pin_vgpr(aVA);
+        bf16x8 bufA[NOP], bufB[NOP];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int kt = 2 * JB + half;      // 32-key tile index inside the chunk
+            const bool active = ANTI ? (kt >= rb) : (kt <= rb);
+            if (!active) continue;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_u((aK ^ (ks << 5)) + half * (32 * ROWB));
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_u((aK ^ ((ks + 4) << 5)) + half * (32 * ROWB));
+            SCHED_FENCE();
+            f32x16 sc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufA[tv] = lds_read_tr8_u((aVA ^ (tv << 6)) + half * (32 * ROWB),
+                                          (aVA ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 8 * ROWB);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufB[tv] = lds_read_tr8_u((aVA ^ (tv << 6)) + half * (32 * ROWB) + 16 * ROWB,
+                                          (aVA ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 24 * ROWB);
+            SCHED_FENCE();
+            if (kt == rb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+                    const bool keep = ANTI ? (key >= l32) : (key <= l32);
+                    sc[v] = keep ? sc[v] : 0.f;
+                }
+            }
+            {
+                u32x4 pk = {pack2(sc[0], sc[1]), pack2(sc[2], sc[3]), pack2(sc[4], sc[5]), pack2(sc[6], sc[7])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
+            }
+            {
+                u32x4 pk = {pack2(sc[8], sc[9]), pack2(sc[10], sc[11]), pack2(sc[12], sc[13]), pack2(sc[14], sc[15])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+            }
+            SCHED_FENCE();
+        }
+    };
+
+    // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
+    auto update = [&]() __attribute__((always_inline)) {
+        uint32_t aXA = lds_addr_of(tK) + uaA, aYA = lds_addr_of(tV) + (uaA ^ ydel);
+        pin_vgpr(aXA); pin_vgpr(aYA);
+        bf16x8 bufA[NOP], bufB[NOP];
+        // operands of 16-token step ks: buf[0] = X^T rows of the wave's tile row, buf[1 + u] = Y
+        // columns of tile u
+        auto rd_upd = [&](bf16x8 (&buf)[NOP], int ks) __attribute__((always_inline)) {
+            buf[0] = lds_read_tr8_u(aXA + ks * (16 * ROWB), (aXA ^ 16) + ks * (16 * ROWB) + 4 * ROWB);
+#pragma unroll
+            for (int u = 0; u < TPW; ++u)
+                buf[1 + u] = lds_read_tr8_u((aYA ^ (u << 6)) + ks * (16 * ROWB),
+                                            (aYA ^ ((u << 6) | 16)) + ks * (16 * ROWB) + 4 * ROWB);
+        };
+        rd_upd(bufA, 0);
+        SCHED_FENCE();
+        rd_upd(bufB, 1);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufA);
+        SCHED_FENCE();
+        rd_upd(bufA, 2);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufB);
+        SCHED_FENCE();
+        rd_upd(bufB, 3);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufA);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufB);
+        SCHED_FENCE();
+    };
+
+    zero_out();
+    using std::integral_constant;
+    for (int c = 0; c < nch; ++c) {
+        const int bi = c * BPC;
+        // the causal walk's last chunk needs the update only for the snapshot between its halves
+        const bool carry = ANTI || c + 1 < nch;
+
+        // The state as the walk enters chunk c: what the rows of its first half start from (causal),
+        // or, negated, the suffix beyond chunk c-1 that the rows of that chunk's second half still
+        // need (anti-causal).  The previous chunk read its last snapshot in block 2; its block 3
+        // barrier lies in between.
+        snapshot();
+
+        // ---- block 0
+        begin(bi);
+        if (!HC1) {
+            // the rows of this chunk (requested in block 2 of the previous one)
+            take_q(wait_vmcnt_token_le(issued - seq_q));
+            if (!ANTI) inter();
+            tiles(integral_constant<int, 0>{});
+        } else {
+            // finish the rows of the previous chunk's second half, request this chunk's
+            if (ANTI) inter();
+            issue_q(c); issued += 8; seq_q = issued;
+            store_rows(c - 1);
+        }
+        update();
+
+        // ---- block 1
+        begin(bi + 1);
+        if (!HC1) tiles(integral_constant<int, 1>{});
+        update();
+
+        // ---- block 2.  Between the halves: every wave has finished block 1 and read the chunk-top
+        // snapshot in block 0.  Causal: rows 128.. start from the state that includes the first
+        // half's keys.  Anti-causal: rows ..127 have seen all keys of their half, and the
+        // accumulators hold minus the suffix beyond it.
+        begin(bi + 2);
+        snapshot();
+        __syncthreads();
+        if (!HC1) {
+            if (ANTI) inter();
+            // the rows of the first half are complete: request the next chunk's, store these
+            issue_q(c + 1); issued += 8; seq_q = issued;
+            store_rows(c);
+        } else {
+            take_q(wait_vmcnt_token_le(issued - seq_q));
+            if (!ANTI) inter();
+            tiles(integral_constant<int, 2>{});
+        }
+        if (carry) update();
+
+        // ---- block 3
+        begin(bi + 3);
+        if (HC1) tiles(integral_constant<int, 3>{});
+        if (carry) update();
+    }
+
+    // The first half's waves requested rows beyond the last chunk in its block 2: let them land in
+    // registers that are still theirs.
+    if (!HC1) {
+        take_q(wait_vmcnt_token<0>());
+        asm volatile("" ::"v"(qv[0]), "v"(qv[1]), "v"(qv[2]), "v"(qv[3]), "v"(qv[4]), "v"(qv[5]), "v"(qv[6]), "v"(qv[7]));
+    }
+    // the last chunk's second half
+    if (ANTI) {
+        snapshot();
+        __syncthreads();
+        if (HC1) inter();
+    }
+    if (HC1) store_rows(nch - 1);
+}
+
+__global__ __launch_bounds__(512) void attn_skew_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
+                                                             AttnProblem p2, int nprob)
+{
+    extern __shared__ __attribute__((aligned(256))) char smem[];
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned unit = (blockIdx.x / (8u * nprob)) * 8u + (blockIdx.x & 7u);
+    const int prob = (int)(blockIdx.x >> 3) % nprob;
+    if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
+    const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
+    const AttnProblem& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    if (len <= 0) return;
+    const int rb = w < 4 ? w : 11 - w;   // waves w and w+4 share a SIMD: row blocks s and 7-s
+    if (rb < 4) {
+        if (pr.anti) skew_walk<false, true>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        else skew_walk<false, false>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+    } else {
+        if (pr.anti) skew_walk<true, true>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        else skew_walk<true, false>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+    }
+}
+
 template <int C>
 hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
                          const AttnProblem& p2, int nprob, hipStream_t st)
@@ -690,6 +1119,20 @@ hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
     dim3 grid(gx), block(C * 2);
     hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, p2, nprob);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_skew(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
+                            const AttnProblem& p2, int nprob, hipStream_t st)
+{
+    constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 8 * 4096;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_skew_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
+    const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
+    dim3 grid(gx), block(512);
+    hipLaunchKernelGGL(attn_skew_mfma_kernel, grid, block, smem, st, g, p0, p1, p2, nprob);
     return hipGetLastError();
 }
 
@@ -1202,7 +1645,7 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
 {
     const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
     if (g.decay) return launch_attn_decay(g, p, p, p, 1, st);
-    if (wide_chunks(g)) return launch_attn_C<256>(g, p, p, p, 1, st);
+    if (wide_chunks(g)) return launch_attn_skew(g, p, p, p, 1, st);
     return launch_attn_C<128>(g, p, p, p, 1, st);
 }
 
@@ -1218,7 +1661,7 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
     if (g.decay) return launch_attn_decay(g, pq, pv, pk, 3, st);
-    if (wide_chunks(g)) return launch_attn_C<256>(g, pq, pv, pk, 3, st);
+    if (wide_chunks(g)) return launch_attn_skew(g, pq, pv, pk, 3, st);
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }
 

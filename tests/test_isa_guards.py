@@ -1,7 +1,7 @@
 """Guards on the compiled attention kernel that no parity test can give: properties of the
 generated gfx950 code the kernel's hand-managed memory waits rely on.  Compiles the kernel file
-to assembly with the flags of the real build (no GPU needed) and checks, for every instantiation
-of attn_mfma_kernel:
+to assembly with the flags of the real build (no GPU needed) and checks, for attn_mfma_kernel<128>
+(the 256-row tiling is attn_skew_mfma_kernel, which has its own tests below):
   * it uses no scratch memory (a spilled register would be reloaded with a vector-memory load the
     explicit wait counts do not account for, and a spill of a register that an in-flight load is
     about to write would save stale data);
@@ -54,7 +54,7 @@ def test_attention_kernels_do_not_spill(isa):
         m = re.search(r"\.amdhsa_kernel " + re.escape(sym) + r".*?\.amdhsa_private_segment_fixed_size (\d+)",
                       text, flags=re.S)
         assert m and int(m.group(1)) == 0, f"attn_mfma_kernel<{cname}> has a private segment"
-    assert found == 2
+    assert found == 1
 
 
 def test_in_flight_row_registers_are_left_alone(isa):
@@ -95,6 +95,105 @@ def test_no_compiler_placed_vmcnt_wait_in_the_walk(isa):
                 in_asm = False
             elif "vmcnt" in l and i > first_barrier:
                 assert in_asm, (cname, i, l.strip())
+
+
+def _skew_blocks(lines):
+    """Basic blocks of attn_skew_mfma_kernel as (loop header or None, [instruction lines])."""
+    start = next(i for i, l in enumerate(lines) if re.match(r"^_ZN.*attn_skew_mfma_kernel.*:", l))
+    end = next(i for i in range(start, len(lines)) if lines[i].startswith(".Lfunc_end"))
+    blocks, cur = [], [None, []]
+    for l in lines[start:end]:
+        m = re.match(r"^(\.LBB\d+_\d+:|; %bb\.\d+:)(.*)", l)
+        if m:
+            blocks.append(cur)
+            h = re.search(r"in Loop: Header=(BB\d+_\d+)", m.group(2))
+            own = re.match(r"^\.L(BB\d+_\d+):", l) if "This Loop Header" in m.group(2) else None
+            cur = [h.group(1) if h else (own.group(1) if own else None), []]
+        else:
+            cur[1].append(l)
+    blocks.append(cur)
+    return lines[start:end], blocks
+
+
+def test_skew_kernel_uses_no_scratch_and_waits_only_where_it_says(isa):
+    """attn_skew_mfma_kernel (four copies of the walk in one function): no scratch memory, and inside
+    its loops no vector-memory wait placed by the compiler (the prologues, outside the loops, wait for
+    the slot state with ordinary loads)."""
+    body, blocks = _skew_blocks(isa)
+    assert not any("scratch_" in l for l in body), "attn_skew_mfma_kernel touches scratch memory"
+    loops = {h for h, ins in blocks if h and any("v_mfma" in l for l in ins)}
+    assert len(loops) == 4, loops            # one walk per half and direction
+    for h, ins in blocks:
+        if h not in loops:
+            continue
+        in_asm = False
+        for l in ins:
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif "vmcnt" in l:
+                assert in_asm, (h, l.strip())
+
+
+def test_skew_kernel_leaves_the_rows_in_flight_alone(isa):
+    """The rows of A are requested with asm loads one or two blocks before they are needed, and taken
+    over by an OR with the zero that the counted wait returns.  Between the request and that OR no
+    instruction may touch the 32 destination registers (a copy made while a load is on its way
+    carries stale data; a request whose registers are dead lets the compiler reuse them at once: that
+    is how a first version of this kernel failed).  Checked in layout order inside each walk's loop:
+    from the request to the OR (second half's waves: block 0 to block 2), or from the request to the
+    loop's end and from its start to the OR (first half's waves: block 2 to the next block 0); and for
+    the requests before the loops, up to their full wait."""
+    body, blocks = _skew_blocks(isa)
+    by_loop = {}
+    for h, ins in blocks:
+        if h:
+            by_loop.setdefault(h, []).extend(ins)
+    checked = 0
+    for h, ins in by_loop.items():
+        if not any("v_mfma" in l for l in ins):
+            continue                      # the walk over the documents of a packed batch
+        code, in_asm = [], False          # (text, inside an asm block)
+        for l in ins:
+            t = l.strip()
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif t and not t.startswith(";") and not t.startswith("."):
+                code.append((t, in_asm))
+        loads = [i for i, (t, a) in enumerate(code) if a and t.startswith("global_load_dwordx4")]
+        assert len(loads) == 8, (h, len(loads))
+        dest = set().union(*(_regs(code[i][0].split(",")[0]) for i in loads))
+        assert len(dest) == 32, (h, len(dest))
+        takes = [i for i, (t, a) in enumerate(code) if not a and t.startswith("v_or_b32") and _regs(t.split(",", 1)[1]) & dest]
+        assert len(takes) == 32, (h, len(takes))
+        first_take, issue = takes[0], loads[-1]
+        regions = [range(issue + 1, first_take)] if first_take > issue else [range(issue + 1, len(code)), range(0, first_take)]
+        for r in regions:
+            for i in r:
+                assert not (_regs(code[i][0]) & dest), (h, code[i][0])
+        checked += 1
+    assert checked == 4
+    # requests before the loops (the first half's walks): nothing touches their registers until the wait
+    in_asm, pending = False, None
+    for h, ins in blocks:
+        if h:
+            pending = None
+            continue
+        for l in ins:
+            t = l.strip()
+            if "#ASMSTART" in l:
+                in_asm = True
+            elif "#ASMEND" in l:
+                in_asm = False
+            elif in_asm and "global_load_dwordx4" in l:
+                pending = (pending or set()) | _regs(l.split(",")[0])
+            elif in_asm and "s_waitcnt vmcnt(0)" in l:
+                pending = None
+            elif not in_asm and pending and t and not t.startswith(";") and not t.startswith("."):
+                assert not (_regs(t) & pending), t
 
 
 def test_decay_attention_kernels_keep_their_loads_in_flight(isa):
