@@ -281,7 +281,7 @@ def main():
                    "state_slots": int(T_s)},
         "ms": {"chunk_states": seg[0], "state_prefix": seg[1], "attn_fwd": seg[2], "attn_bwd": seg[3]},
         "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
-        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel<256>, average of its two launches per step",
+        "roofline": {"bound": "hbm", "kernel": "attn_skew_mfma_kernel, average of its two launches per step",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": avg_ms, "fwd_launch_ms": t_fwd, "bwd_launch_ms": t_bwd,

@@ -451,13 +451,6 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     // round-robin placement) get blocks s and 7-s, so that their triangular work adds up evenly.
     const int rb = (NW == 8) ? (w < 4 ? w : 11 - w) : w;
     const int t0 = w * TPW;
-    // With 256 rows per chunk the masked products are taken over the chunk's two 128-row halves
-    // separately (half hc of the rows against the same half of the keys only), and the half that
-    // lies further along the walk reads a second state snapshot taken between the halves: the
-    // same sum, with 44 % fewer score tiles than one 256-row triangle.
-    constexpr bool SPLIT = (C == 256);
-    const int hc = SPLIT ? (rb >> 2) : 0;
-
     const int nch = (len + C - 1) / C;
     const int NB = (len + KB - 1) / KB;    // 64-token blocks in the whole slot
     uint32_t dvo[16 / NW];   // per-lane source offsets of this wave's stage loads
@@ -560,16 +553,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             __syncthreads();   // block bi complete in LDS; every wave is past block bi-1
             if (bi + 2 < NB) issue(bi + 2);
 
-            if (!anti && jb == 0 && hc == 0) inter_product<NOP>(Oacc, sM, qf, lo.nat);
-            if (SPLIT && jb == 2) {
-                // Between the halves: every wave has finished block 1 (this block's barrier) and read
-                // the previous snapshot long ago.  Causal: rows 128.. start from the state that
-                // includes the first half's keys.  Anti-causal: rows ..127 have now seen all keys of
-                // their half, and the accumulators hold minus the suffix beyond it.
-                write_snapshot<TPW>(sM, Macc, t0, l32, h, anti != 0);
-                __syncthreads();
-                if (hc == (anti ? 0 : 1)) inter_product<NOP>(Oacc, sM, qf, lo.nat);
-            }
+            if (!anti && jb == 0) inter_product<NOP>(Oacc, sM, qf, lo.nat);
 
             // Operand fetches are issued a batch ahead of the MFMAs that consume them (two
             // small register buffers); sched_barrier keeps the compiler from sinking the
@@ -578,7 +562,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int kt = 2 * jb + half;      // 32-key tile index inside the chunk
-                const bool active = (anti ? (kt >= rb) : (kt <= rb)) && (!SPLIT || (kt >> 2) == hc);
+                const bool active = anti ? (kt >= rb) : (kt <= rb);
                 if (!active) continue;
                 // scores^T (keys x queries) = Bk_tile A_w^T ; the Cv operands of the second
                 // product are fetched while the first one runs
@@ -631,8 +615,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
             // causal: the rows of the next chunk replace qf while the state update and the
             // store run (anti-causal still needs qf for the inter product at the chunk's end)
             if (!anti && jb + 1 == nblk && !last_chunk) issue_q(c + 1);
-            // (the causal walk's last chunk needs the update only for the snapshot between its halves)
-            if (anti || !last_chunk || (SPLIT && jb < 2 && nblk > 2)) {
+            if (anti || !last_chunk) {
                 // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
                 rd_update<TPW, NOP>(bufA, tK, tV, 0, lo);
                 SCHED_FENCE();
@@ -655,13 +638,10 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
         if (anti) {
             // every wave read the previous snapshot before its previous store, and at least one
-            // block barrier has passed since (with three blocks the snapshot between the halves was
-            // read inside the last block: one more barrier)
-            if (SPLIT && nblk == 3) __syncthreads();
+            // block barrier has passed since
             write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
             __syncthreads();
-            // rows of the second half; of the first half too when the chunk ends inside it
-            if (!SPLIT || hc == 1 || nblk <= 2) inter_product<NOP>(Oacc, sM, qf, lo.nat);
+            inter_product<NOP>(Oacc, sM, qf, lo.nat);
             if (!last_chunk) issue_q(c + 1);
         }
 
@@ -704,12 +684,20 @@ __device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
     return wait_vmcnt_token<0>();
 }
 
-// The fused pass with 256-row chunks, the work of the two 128-row halves skewed against each
-// other.  Same problems, grid, tiles, stages and walk as attn_mfma_kernel<256>; the difference is
-// when a wave finishes its rows.  A 64-token block concerns the rows of one half only, so at any
-// time the four waves of the other half have nothing but their share of the state update to do.
-// Here they use that time for what attn_mfma_kernel does with all eight waves at the end of a
-// chunk:
+// The fused pass with 256-row chunks and eight waves (slots longer than 128 tokens).  Same
+// problems, grid, tiles, stages, walk directions and asynchronous fetches as attn_mfma_kernel;
+// waves w and w+4, which share a SIMD, own row blocks w and 7-w.  Two differences:
+//
+// Halves.  The masked products of a chunk are taken over its two 128-row halves separately:
+// rows of a half against the keys of the same half only, and the half that lies further along
+// the walk reads a second state snapshot taken between the halves (causal: rows 128.. start from
+// the state that includes the first half's keys; anti-causal: rows ..127 have then seen all keys
+// of their half and the accumulators hold minus the suffix beyond it).  The same sum, with 20
+// score tiles per chunk instead of 36.
+//
+// Skew.  A 64-token block therefore concerns the rows of one half only, and at any time the
+// four waves of the other half have nothing but their share of the state update to do.  They use
+// that time for the work that would otherwise stop all eight waves at the end of a chunk:
 //   - rows of the first half are complete once block 1 has been consumed (anti-causal: once the
 //     state between the halves has been applied, at block 2): their waves fetch the next chunk's
 //     rows and store during blocks 2 and 3, while the second half's waves compute;
@@ -758,8 +746,8 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     issue(0);
     if (KB < len) issue(1);
 
-    // running state tiles, C/D layout: rows = d_k (first index), columns = d_v; negated for the
-    // anti-causal walk (see attn_mfma_kernel)
+    // running state tiles, C/D layout: rows = d_k (first index), columns = d_v; the anti-causal
+    // walk keeps minus the inclusive suffix and adds the blocks it passes (see attn_mfma_kernel)
     f32x16 Macc[TPW];
     {
         const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
