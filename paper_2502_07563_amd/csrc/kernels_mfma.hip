@@ -699,21 +699,25 @@ __device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
 // four waves of the other half have nothing but their share of the state update to do.  They use
 // that time for the work that would otherwise stop all eight waves at the end of a chunk:
 //   - rows of the first half are complete once block 1 has been consumed (anti-causal: once the
-//     state between the halves has been applied, at block 2): their waves fetch the next chunk's
-//     rows and store during blocks 2 and 3, while the second half's waves compute;
+//     state between the halves has been applied, at block 2): their waves request the next
+//     chunk's rows in block 2 and store in block 3, while the second half's waves compute;
 //   - rows of the second half are complete at the end of the chunk (anti-causal: once the state
-//     at the chunk's end has been applied): their waves keep the accumulators, and finish and
-//     store during block 0 of the next chunk, while the first half's waves compute.  The
-//     snapshot taken at the top of a chunk is therefore the state the previous chunk's second
-//     half still needs (anti-causal) as well as the one this chunk's first half starts from
-//     (causal), and needs no barrier of its own: block 0's barrier publishes it.
+//     at the chunk's end has been applied): their waves keep the accumulators, finish them and
+//     request their next rows in block 0 of the next chunk and store in block 1, while the first
+//     half's waves compute.  The snapshot taken at the top of a chunk is therefore the state the
+//     previous chunk's second half still needs (anti-causal) as well as the one this chunk's
+//     first half starts from (causal).
+// Neither snapshot needs a barrier of its own: each is written at the end of a block's work (after
+// block 3: the top of the next chunk; after block 1: between the halves), when every wave has
+// passed that block's barrier and with it all reads of the previous snapshot, and the next
+// block's barrier publishes it.
 // The two halves' waves and the two directions run separate copies of the walk (HC1, ANTI), each
 // a straight line through the four blocks of a chunk, so that the accumulators and the rows in
 // flight have one definition per place and are not copied at control-flow joins.  Every chunk is
 // walked as four blocks: a block that lies wholly past the slot's end is not loaded but zeroed, and
-// contributes nothing.  All copies pass the same barriers: one per block, one between the halves,
-// and for the anti-causal walk one at the end.  Each half stores at a different time, so the
-// waits are counted at run time (wait_vmcnt_le).
+// contributes nothing.  All copies pass the same barriers: one per block, and for the anti-causal
+// walk one at the end.  Each half stores at a different time, so the waits are counted at run
+// time (wait_vmcnt_le).
 template <bool HC1, bool ANTI>
 __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, char* smem, int tid, int w,
                                           int rb, int grp, int s, int tok0, int len)
@@ -777,14 +781,13 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     //   transposed fetch of columns 32 tv + l32, rows r:   pvA ^ (tv << 6);  rows r + 8: (.. ^ 32) + 8 rows
     //   state update, X^T operand, rows r:                 uaA;              rows r + 4: (uaA ^ 16) + 4 rows
     //   state update, Y operand of tile u:                 uaA ^ ydel ^ (u << 6), ydel the same in all lanes
-    //   snapshot piece q of tile u:                        (snp0 ^ (q << 4)) + u * 32 rows
+    //   snapshot piece q of tile u:                        (s0 ^ (q << 4)) + u * 32 rows, s0 rebuilt at each snapshot
     // (a stage's base is a multiple of its 16 KiB, so base + offset can be formed first).
     const int li = lane & 15, g2 = (lane >> 4) & 1, cl = 16 * g2 + 4 * (li & 3), rl = li >> 2;
     const uint32_t nat0 = (uint32_t)tile_off(l32, h);
     const uint32_t pvA = (uint32_t)tr_off(4 * h + rl, cl);
     const uint32_t uaA = (uint32_t)tr_off(8 * h + rl, 32 * (t0 >> 2) + cl);
     const uint32_t ydel = (uint32_t)(((t0 >> 2) ^ (t0 & 3)) << 6);
-    const uint32_t snp0 = lds_addr_of(sM) + (uint32_t)tile_off(32 * (t0 & 3) + l32, 4 * (t0 >> 2)) + 8 * h;
 
     // this wave's 32 rows of A as B-operand fragments, fetched asynchronously (see attn_mfma_kernel);
     // rows past the slot's end fetch its last row
@@ -822,8 +825,9 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     // snapshot of the running state, bf16 [d_v][d_k] (the anti-causal walk holds minus the state)
     auto snapshot = [&]() __attribute__((always_inline)) {
         const float sg = ANTI ? -1.f : 1.f;
-        uint32_t s0 = snp0;
-        pin_vgpr(s0);   // keeps the eight addresses from being formed once and held
+        int ln;   // built here from the lane index (twice per chunk) rather than held in a register
+        asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+        const uint32_t s0 = lds_addr_of(sM) + (uint32_t)tile_off(32 * (t0 & 3) + (ln & 31), 4 * (t0 >> 2)) + 8 * (ln >> 5);
 #pragma unroll
         for (int u = 0; u < TPW; ++u)
 #pragma unroll
@@ -941,10 +945,15 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
                                           (aVA ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 24 * ROWB);
             SCHED_FENCE();
             if (kt == rb) {
+                // the diagonal tile's mask, from a lane index the compiler cannot hoist: hoisted, the 16
+                // predicates would occupy 32 scalar registers across the whole walk
+                int ln;
+                asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+                const int lq = ln & 31, hq = ln >> 5;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = 8 * (v >> 2) + 4 * h + (v & 3);
-                    const bool keep = ANTI ? (key >= l32) : (key <= l32);
+                    const int key = 8 * (v >> 2) + 4 * hq + (v & 3);
+                    const bool keep = ANTI ? (key >= lq) : (key <= lq);
                     sc[v] = keep ? sc[v] : 0.f;
                 }
             }
@@ -1020,27 +1029,26 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
             // finish the rows of the previous chunk's second half, request this chunk's
             if (ANTI) inter();
             issue_q(c); issued += 8; seq_q = issued;
-            store_rows(c - 1);
         }
         update();
 
-        // ---- block 1
+        // ---- block 1 (the second half's waves have nothing else to do here: they store)
         begin(bi + 1);
         if (!HC1) tiles(integral_constant<int, 1>{});
+        else store_rows(c - 1);
         update();
-
-        // ---- block 2.  Between the halves: every wave has finished block 1 and read the chunk-top
-        // snapshot in block 0.  Causal: rows 128.. start from the state that includes the first
-        // half's keys.  Anti-causal: rows ..127 have seen all keys of their half, and the
-        // accumulators hold minus the suffix beyond it.
-        begin(bi + 2);
+        // The state between the halves.  Every wave has passed block 1's barrier, so the reads of the
+        // chunk-top snapshot (in block 0) are over; block 2's barrier publishes this one.  Causal: rows
+        // 128.. start from the state that includes the first half's keys.  Anti-causal: rows ..127 have
+        // seen all keys of their half, and the accumulators hold minus the suffix beyond it.
         snapshot();
-        __syncthreads();
+
+        // ---- block 2
+        begin(bi + 2);
         if (!HC1) {
             if (ANTI) inter();
-            // the rows of the first half are complete: request the next chunk's, store these
+            // the rows of the first half are complete: request the next chunk's
             issue_q(c + 1); issued += 8; seq_q = issued;
-            store_rows(c);
         } else {
             take_q(wait_vmcnt_token_le(issued - seq_q));
             if (!ANTI) inter();
@@ -1048,9 +1056,10 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
         }
         if (carry) update();
 
-        // ---- block 3
+        // ---- block 3 (the first half's waves store here)
         begin(bi + 3);
         if (HC1) tiles(integral_constant<int, 3>{});
+        else store_rows(c);
         if (carry) update();
     }
 

@@ -167,7 +167,11 @@ def test_skew_kernel_leaves_the_rows_in_flight_alone(isa):
         assert len(loads) == 8, (h, len(loads))
         dest = set().union(*(_regs(code[i][0].split(",")[0]) for i in loads))
         assert len(dest) == 32, (h, len(dest))
-        takes = [i for i, (t, a) in enumerate(code) if not a and t.startswith("v_or_b32") and _regs(t.split(",", 1)[1]) & dest]
+        ors = [i for i, (t, a) in enumerate(code) if not a and t.startswith("v_or_b32") and _regs(t.split(",", 1)[1]) & dest]
+        # the take-over ORs share the wait's zero as their other operand (a later reuse of a freed
+        # register in some other OR is not one of them)
+        zero = code[ors[0]][0].split(",")[1].strip()
+        takes = [i for i in ors if code[i][0].split(",")[1].strip() == zero]
         assert len(takes) == 32, (h, len(takes))
         first_take, issue = takes[0], loads[-1]
         regions = [range(issue + 1, first_take)] if first_take > issue else [range(issue + 1, len(code)), range(0, first_take)]
