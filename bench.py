@@ -289,7 +289,7 @@ def main():
                      "device_copy_GBps": copy_gbps},
     }
     if args.decay:
-        out["roofline"]["kernel"] = "attn_decay_mfma_kernel, average of its two launches per step"
+        out["roofline"]["kernel"] = "attn_skew_mfma_kernel<decay>, average of its two launches per step"
         out["roofline"]["traffic"] = None
     if not args.no_cpu_baseline and not args.decay:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)

@@ -711,6 +711,9 @@ __device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
 // block 3: the top of the next chunk; after block 1: between the halves), when every wave has
 // passed that block's barrier and with it all reads of the previous snapshot, and the next
 // block's barrier publishes it.
+// With scalar decay (DECAY; weights as in attn_decay_mfma_kernel) the anti-causal problems walk
+// backwards and every half takes its state on entry, like the causal ones; "first" and "second"
+// half above then mean the order in which the walk reaches them.
 // The two halves' waves and the two directions run separate copies of the walk (HC1, ANTI), each
 // a straight line through the four blocks of a chunk, so that the accumulators and the rows in
 // flight have one definition per place and are not copied at control-flow joins.  Every chunk is
@@ -718,11 +721,17 @@ __device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
 // contributes nothing.  All copies pass the same barriers: one per block, and for the anti-causal
 // walk one at the end.  Each half stores at a different time, so the waits are counted at run
 // time (wait_vmcnt_le).
-template <bool HC1, bool ANTI>
+template <bool HC1, bool ANTI, bool DECAY>
 __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, char* smem, int tid, int w,
                                           int rb, int grp, int s, int tok0, int len)
 {
     constexpr int C = 256, NW = 8, TPW = 2, BPC = 4, DPS = 4, NOP = 4;
+    // With decay the anti-causal problems walk the slot backwards from the exclusive suffix (see
+    // attn_decay_mfma_kernel), so both directions take their states when the walk enters a half;
+    // without it they walk forwards and subtract (see attn_mfma_kernel), and take them when it leaves.
+    constexpr bool REV = DECAY && ANTI;        // blocks and chunks in descending order
+    constexpr bool ENDSTATE = ANTI && !DECAY;  // rows take the state at the end of their half
+    constexpr bool SECOND = REV ? !HC1 : HC1;  // this wave's rows lie in the half the walk reaches second
     char* sK = smem;                              // Bk stages
     char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
     char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
@@ -735,8 +744,14 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
     const int t0 = w * TPW;
     const int nch = (len + C - 1) / C;
+    const int NBP = nch * BPC;                 // blocks walked (the last chunk padded to four)
+    const float l2 = DECAY ? uniform_f32(decay_log2(g, grp)) : 0.f;   // log2 of the head's factor
+    const float wblk = DECAY ? uniform_f32(exp2f((float)KB * l2)) : 1.f;
+    // walk position -> block of the slot, chunk of the slot
+    auto blk = [&](int i) __attribute__((always_inline)) { return REV ? NBP - 1 - i : i; };
+    auto chk = [&](int c) __attribute__((always_inline)) { return REV ? nch - 1 - c : c; };
 
-    // Stage loads of block i.  The per-lane source offsets are rebuilt at every call from a lane index
+    // Stage loads of the block at walk position i.  The per-lane source offsets are rebuilt at every call from a lane index
     // the compiler cannot hoist: kept across the walk they cost registers this kernel does not have.
     auto issue = [&](int i) __attribute__((always_inline)) {
         int ln;
@@ -744,18 +759,18 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
         uint32_t dvo[16 / NW];
 #pragma unroll
         for (int u = 0; u < 16 / NW; ++u) dvo[u] = dma_lane_off(w * (16 / NW) + u, ln);
-        dma_block<NW>(Bk, Cv, row0, i * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
+        dma_block<NW>(Bk, Cv, row0, blk(i) * KB, len, sK + (i % NSTAGE) * STAGE_BYTES,
                       sV + (i % NSTAGE) * STAGE_BYTES, w, ln, dvo);
     };
-    issue(0);
-    if (KB < len) issue(1);
+    if (blk(0) * KB < len) issue(0);
+    if (blk(1) * KB < len) issue(1);
 
     // running state tiles, C/D layout: rows = d_k (first index), columns = d_v; the anti-causal
     // walk keeps minus the inclusive suffix and adds the blocks it passes (see attn_mfma_kernel)
     f32x16 Macc[TPW];
     {
         const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
-        const float sg = ANTI ? -1.f : 1.f;
+        const float sg = ENDSTATE ? -1.f : 1.f;
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
             const int t = t0 + u, a = t >> 2, b = t & 3;
@@ -792,10 +807,10 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     // this wave's 32 rows of A as B-operand fragments, fetched asynchronously (see attn_mfma_kernel);
     // rows past the slot's end fetch its last row
     u32x4 qv[8];
-    auto issue_q = [&](int c) __attribute__((always_inline)) {
+    auto issue_q = [&](int c) __attribute__((always_inline)) {   // c: chunk of the slot
         int ln;   // the lane index again, in a form the compiler cannot hoist out of the loop (and spill)
         asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
-        const int r = min(c * C + 32 * rb + (ln & 31), len - 1);
+        const int r = max(min(c * C + 32 * rb + (ln & 31), len - 1), 0);
         const char* p = A + row0 + (size_t)r * ROWB + 16 * (ln >> 5);
         gload16_async<0>(qv[0], p);
         gload16_async<32>(qv[1], p);
@@ -814,17 +829,17 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     // The first half's waves need the rows of chunk 0 at once; the second half's request theirs in
     // block 0.  (A request whose registers are never read afterwards must not be made: the compiler
     // would reuse those registers while the load is still on its way.)
-    if (!HC1) {
-        issue_q(0);
+    if (!SECOND) {
+        issue_q(chk(0));
         take_q(wait_vmcnt_token<0>());   // also completes blocks 0 and 1 and the state
     } else {
         wait_vmcnt<0>();
     }
     const bf16x8 (&qf)[8] = reinterpret_cast<const bf16x8 (&)[8]>(qv);
 
-    // snapshot of the running state, bf16 [d_v][d_k] (the anti-causal walk holds minus the state)
+    // snapshot of the running state, bf16 [d_v][d_k] (the subtracting walk holds minus the state)
     auto snapshot = [&]() __attribute__((always_inline)) {
-        const float sg = ANTI ? -1.f : 1.f;
+        const float sg = ENDSTATE ? -1.f : 1.f;
         int ln;   // built here from the lane index (twice per chunk) rather than held in a register
         asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
         const uint32_t s0 = lds_addr_of(sM) + (uint32_t)tile_off(32 * (t0 & 3) + (ln & 31), 4 * (t0 >> 2)) + 8 * (ln >> 5);
@@ -873,15 +888,31 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
             SCHED_FENCE();
         }
     };
+    // With decay the state sits one token before the rows' half (causal) or one after it
+    // (anti-causal): weight per query.  The accumulators hold nothing else yet.
+    auto inter_decayed = [&](int cc) __attribute__((always_inline)) {
+        inter();
+        int ln;
+        asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+        const int a = 32 * rb + (ln & 31), hb = HC1 ? 1 : 0;
+        const int clen = min(C, len - cc * C);
+        const int e = REV ? max(min(clen, 128 * (hb + 1)) - a, 0) : a - 128 * hb + 1;
+        const float wq = __builtin_amdgcn_exp2f((float)e * l2);
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Oacc[tv][v] *= wq;
+    };
 
     // vector-memory instructions certainly issued since the full wait above, and the marks of the
     // batches to wait for
     int issued = 0, seq_cur = 0, seq_next = 0, seq_q = 0;
 
-    // stores this wave's rows of chunk c (none when c < 0) and clears the accumulators
+    // stores this wave's rows of chunk c of the slot (none when there is no such chunk) and clears
+    // the accumulators
     auto store_rows = [&](int c) __attribute__((always_inline)) {
         const int rbase = c * C + 32 * rb;
-        const int nrows = c < 0 ? 0 : len - rbase;
+        const int nrows = (c < 0 || c >= nch) ? 0 : len - rbase;
         store_out_rows(Oacc, sO + w * 4096, out + row0 + (ptrdiff_t)rbase * ROWB, nrows, tid);
         if (nrows >= 32) issued += 8;   // all eight stores certainly execute
         SCHED_FENCE();
@@ -892,27 +923,43 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     char* tV = sV;
     // start of block bi: its loads have landed, the block is complete in LDS, every wave is past
     // block bi - 1, and the loads of block bi + 2 are on their way
-    auto begin = [&](int bi) __attribute__((always_inline)) {
+    auto begin = [&](int bi) __attribute__((always_inline)) {   // bi: walk position
         tK = sK + (bi % NSTAGE) * STAGE_BYTES;
         tV = sV + (bi % NSTAGE) * STAGE_BYTES;
         wait_vmcnt_le(issued - seq_cur);
-        if (bi * KB + KB > len) {   // at the slot's end only: keep these addresses out of the walk's registers
+        if (blk(bi) * KB + KB > len) {   // at the slot's end only: keep these addresses out of the walk's registers
             int ln;
             asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
-            zero_tail_rows<NW>(bi * KB, len, tK, tV, w, ln);
+            zero_tail_rows<NW>(blk(bi) * KB, len, tK, tV, w, ln);
+        }
+        if (DECAY) {
+            // Weight this wave's own rows of the Bk tile by the token's factor as seen from the
+            // block's last token (forward walk, lam^(63-b)) or first token (backward walk, lam^b); a
+            // whole row takes one weight, so the swizzle does not matter here.
+            int ln;
+            asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+#pragma unroll
+            for (int u = 0; u < 16 / NW; ++u) {
+                const int b = 4 * (w * (16 / NW) + u) + (ln >> 4);
+                const float wr = __builtin_amdgcn_exp2f((float)(REV ? b : KB - 1 - b) * l2);
+                u32x4* pk = reinterpret_cast<u32x4*>(tK + b * ROWB + (ln & 15) * 16);
+                *pk = scale_bf16x8(*pk, wr);
+            }
         }
         __syncthreads();
         seq_cur = seq_next;
-        if ((bi + 2) * KB < len) { issue(bi + 2); issued += DPS; }
+        if (bi + 2 < NBP && blk(bi + 2) * KB < len) { issue(bi + 2); issued += DPS; }
         seq_next = issued;
     };
 
     // masked products of this wave's rows with the two 32-key tiles of block JB of the chunk
-    auto tiles = [&](auto jb_c) __attribute__((always_inline)) {
-        constexpr int JB = decltype(jb_c)::value;
+    auto tiles = [&](auto jw_c) __attribute__((always_inline)) {
+        constexpr int JB = REV ? 3 - decltype(jw_c)::value : decltype(jw_c)::value;   // block of the chunk
         // per-lane addresses into this block's stage, opaque to the compiler: it would otherwise fold
         // the constants of every use into copies that it keeps (and spills) across the whole walk
-        uint32_t aK = lds_addr_of(tK) + nat0, aVA = lds_addr_of(tV) + pvA;
+        uint32_t oK = nat0, oV = pvA;
+        pin_vgpr(oK); pin_vgpr(oV);   // (opaque before the sum too: no table of sums per stage)
+        uint32_t aK = lds_addr_of(tK) + oK, aVA = lds_addr_of(tV) + oV;
         pin_vgpr(aK); pin_vgpr(aVA);
         bf16x8 bufA[NOP], bufB[NOP];
 #pragma unroll
@@ -944,6 +991,16 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
                 bufB[tv] = lds_read_tr8_u((aVA ^ (tv << 6)) + half * (32 * ROWB) + 16 * ROWB,
                                           (aVA ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 24 * ROWB);
             SCHED_FENCE();
+            if (DECAY) {
+                // from the row weights of the block to lam^|i-j|: one factor per query; query and keys
+                // lie in the same 128-row half, so the exponent stays within -63..64
+                int ln;
+                asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+                const int qi = 32 * rb + (ln & 31) - KB * JB;   // query index relative to the block's start
+                const float f = __builtin_amdgcn_exp2f((float)(REV ? -qi : qi - (KB - 1)) * l2);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sc[v] *= f;
+            }
             if (kt == rb) {
                 // the diagonal tile's mask, from a lane index the compiler cannot hoist: hoisted, the 16
                 // predicates would occupy 32 scalar registers across the whole walk
@@ -974,8 +1031,19 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     };
 
     // running state += Bk_blk^T Cv_blk on this wave's tiles, 16 tokens per step
-    auto update = [&]() __attribute__((always_inline)) {
-        uint32_t aXA = lds_addr_of(tK) + uaA, aYA = lds_addr_of(tV) + (uaA ^ ydel);
+    auto update = [&](int bi) __attribute__((always_inline)) {   // bi: walk position
+        if (DECAY) {
+            // state = lam^n * state + (weighted Bk block)^T Cv block, n = the block's tokens
+            const int n = min(max(len - blk(bi) * KB, 0), KB);
+            const float wb = n == KB ? wblk : __builtin_amdgcn_exp2f((float)n * l2);
+#pragma unroll
+            for (int u = 0; u < TPW; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) Macc[u][v] *= wb;
+        }
+        uint32_t oX = uaA;
+        pin_vgpr(oX);   // (opaque before the sums too: no table of sums per stage)
+        uint32_t aXA = lds_addr_of(tK) + oX, aYA = lds_addr_of(tV) + (oX ^ ydel);
         pin_vgpr(aXA); pin_vgpr(aYA);
         bf16x8 bufA[NOP], bufB[NOP];
         // operands of 16-token step ks: buf[0] = X^T rows of the wave's tile row, buf[1 + u] = Y
@@ -1007,77 +1075,82 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
 
     zero_out();
     using std::integral_constant;
-    for (int c = 0; c < nch; ++c) {
-        const int bi = c * BPC;
-        // the causal walk's last chunk needs the update only for the snapshot between its halves
-        const bool carry = ANTI || c + 1 < nch;
+    for (int c = 0; c < nch; ++c) {   // c: walk position of the chunk; cc: the chunk of the slot
+        const int bi = c * BPC, cc = chk(c);
+        // a walk that takes its states on entering a half needs the last chunk's update only for
+        // the snapshot between its halves
+        const bool carry = ENDSTATE || c + 1 < nch;
 
-        // The state as the walk enters chunk c: what the rows of its first half start from (causal),
-        // or, negated, the suffix beyond chunk c-1 that the rows of that chunk's second half still
-        // need (anti-causal).  The previous chunk read its last snapshot in block 2; its block 3
+        // The state as the walk enters the chunk: what the rows of its first half start from, or
+        // (subtracting walk) the suffix beyond the previous chunk that the rows of that chunk's
+        // second half still need.  The previous chunk read its last snapshot in block 2; its block 3
         // barrier lies in between.
         snapshot();
 
         // ---- block 0
         begin(bi);
-        if (!HC1) {
+        if (!SECOND) {
             // the rows of this chunk (requested in block 2 of the previous one)
             take_q(wait_vmcnt_token_le(issued - seq_q));
-            if (!ANTI) inter();
+            if (DECAY) inter_decayed(cc);
+            else if (!ENDSTATE) inter();
             tiles(integral_constant<int, 0>{});
         } else {
             // finish the rows of the previous chunk's second half, request this chunk's
-            if (ANTI) inter();
-            issue_q(c); issued += 8; seq_q = issued;
+            if (ENDSTATE) inter();
+            issue_q(cc); issued += 8; seq_q = issued;
         }
-        update();
+        update(bi);
 
         // ---- block 1 (the second half's waves have nothing else to do here: they store)
         begin(bi + 1);
-        if (!HC1) tiles(integral_constant<int, 1>{});
-        else store_rows(c - 1);
-        update();
+        if (!SECOND) tiles(integral_constant<int, 1>{});
+        else store_rows(REV ? cc + 1 : cc - 1);
+        update(bi + 1);
         // The state between the halves.  Every wave has passed block 1's barrier, so the reads of the
-        // chunk-top snapshot (in block 0) are over; block 2's barrier publishes this one.  Causal: rows
-        // 128.. start from the state that includes the first half's keys.  Anti-causal: rows ..127 have
-        // seen all keys of their half, and the accumulators hold minus the suffix beyond it.
+        // chunk-top snapshot (in block 0) are over; block 2's barrier publishes this one.  Entering
+        // walks: the second half starts from the state that includes the first half's keys.
+        // Subtracting walk: rows ..127 have seen all keys of their half, and the accumulators hold
+        // minus the suffix beyond it.
         snapshot();
 
         // ---- block 2
         begin(bi + 2);
-        if (!HC1) {
-            if (ANTI) inter();
+        if (!SECOND) {
+            if (ENDSTATE) inter();
             // the rows of the first half are complete: request the next chunk's
-            issue_q(c + 1); issued += 8; seq_q = issued;
+            issue_q(REV ? cc - 1 : cc + 1); issued += 8; seq_q = issued;
         } else {
             take_q(wait_vmcnt_token_le(issued - seq_q));
-            if (!ANTI) inter();
+            if (DECAY) inter_decayed(cc);
+            else if (!ENDSTATE) inter();
             tiles(integral_constant<int, 2>{});
         }
-        if (carry) update();
+        if (carry) update(bi + 2);
 
         // ---- block 3 (the first half's waves store here)
         begin(bi + 3);
-        if (HC1) tiles(integral_constant<int, 3>{});
-        else store_rows(c);
-        if (carry) update();
+        if (SECOND) tiles(integral_constant<int, 3>{});
+        else store_rows(cc);
+        if (carry) update(bi + 3);
     }
 
     // The first half's waves requested rows beyond the last chunk in its block 2: let them land in
     // registers that are still theirs.
-    if (!HC1) {
+    if (!SECOND) {
         take_q(wait_vmcnt_token<0>());
         asm volatile("" ::"v"(qv[0]), "v"(qv[1]), "v"(qv[2]), "v"(qv[3]), "v"(qv[4]), "v"(qv[5]), "v"(qv[6]), "v"(qv[7]));
     }
     // the last chunk's second half
-    if (ANTI) {
+    if (ENDSTATE) {
         snapshot();
         __syncthreads();
-        if (HC1) inter();
+        if (SECOND) inter();
     }
-    if (HC1) store_rows(nch - 1);
+    if (SECOND) store_rows(chk(nch - 1));
 }
 
+template <bool DECAY>
 __global__ __launch_bounds__(512) void attn_skew_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
                                                              AttnProblem p2, int nprob)
 {
@@ -1094,11 +1167,11 @@ __global__ __launch_bounds__(512) void attn_skew_mfma_kernel(Geom g, AttnProblem
     if (len <= 0) return;
     const int rb = w < 4 ? w : 11 - w;   // waves w and w+4 share a SIMD: row blocks s and 7-s
     if (rb < 4) {
-        if (pr.anti) skew_walk<false, true>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
-        else skew_walk<false, false>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        if (pr.anti) skew_walk<false, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        else skew_walk<false, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
     } else {
-        if (pr.anti) skew_walk<true, true>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
-        else skew_walk<true, false>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        if (pr.anti) skew_walk<true, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        else skew_walk<true, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
     }
 }
 
@@ -1119,17 +1192,19 @@ hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem
     return hipGetLastError();
 }
 
+template <bool DECAY>
 hipError_t launch_attn_skew(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
                             const AttnProblem& p2, int nprob, hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 8 * 4096;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_skew_mfma_kernel),
+    auto kern = attn_skew_mfma_kernel<DECAY>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
     dim3 grid(gx), block(512);
-    hipLaunchKernelGGL(attn_skew_mfma_kernel, grid, block, smem, st, g, p0, p1, p2, nprob);
+    hipLaunchKernelGGL(kern, grid, block, smem, st, g, p0, p1, p2, nprob);
     return hipGetLastError();
 }
 
@@ -1146,22 +1221,21 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
 
 // =====================================================================================
 // Fused attention pass with scalar decay: out_i = sum_j lam^|i-j| (a_i . bk_j) cv_j over the
-// allowed pairs plus the decayed inter-chunk term.  Same tiles, stages, layouts, wave placement
-// and asynchronous fetches as attn_mfma_kernel<C> (256 rows with eight waves, or 128 with four),
-// with these differences:
+// allowed pairs plus the decayed inter-chunk term, for slots of at most 128 tokens (longer ones:
+// skew_walk with DECAY).  Same tiles, stages, layouts and asynchronous fetches as
+// attn_mfma_kernel<128>, with these differences:
 //   - Anti-causal problems walk the slot BACKWARDS (blocks and chunks in descending order, the
 //     slot state being the exclusive suffix): with decay the forward walk with a subtracted
 //     suffix would have to divide by lam at every step.  Both directions therefore take the
-//     state snapshot and the inter-chunk product when the walk enters a chunk, and, with 256
-//     rows, a second time when it enters the chunk's other 128-row half.
+//     state snapshot and the inter-chunk product when the walk enters a chunk.
 //   - Each wave multiplies the rows of the Bk tile it staged by the token's weight as seen from
 //     the block's last token (causal, lam^(63-b)) or first token (anti-causal, lam^b) before the
 //     block barrier.  The state update then is lam^64 * state + Bk~^T Cv, and a score computed
 //     from the weighted rows needs only a factor per query, lam^(i - block start - 63) resp.
 //     lam^(block start - i), to become lam^|i-j| (a_i . bk_j); a query and the keys it meets lie
-//     in the same 128-row half, so the exponents stay within -63..64.
-//   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the half)
-//     or lam^(end of the half - a) (anti-causal).
+//     in the same 128 rows, so the exponents stay within -63..64.
+//   - The inter-chunk product is scaled per query by lam^(a+1) (causal, a = index in the chunk)
+//     or lam^(chunk length - a) (anti-causal).
 // =====================================================================================
 template <int C>
 __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProblem p0, AttnProblem p1,
@@ -1169,7 +1243,6 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
 {
     constexpr int NW = C / 32, TPW = 16 / NW, BPC = C / KB, IPW = 16 / NW, DPS = 2 * IPW;
     constexpr int NOP = (TPW + 1 > 4) ? 8 : 4;
-    constexpr bool SPLIT = (C == 256);
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* sK = smem;                              // Bk stages
     char* sV = smem + NSTAGE * STAGE_BYTES;       // Cv stages
@@ -1195,7 +1268,6 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
     const float l2 = uniform_f32(decay_log2(g, grp));   // one value per workgroup: scalar
     const int rb = (NW == 8) ? (w < 4 ? w : 11 - w) : w;   // as in attn_mfma_kernel
-    const int hc = SPLIT ? (rb >> 2) : 0;                  // the 128-row half this wave's rows lie in
     const int t0 = w * TPW;
 
     const int nch = (len + C - 1) / C;
@@ -1314,23 +1386,14 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
             __syncthreads();   // block complete and weighted in LDS; every wave is past the previous one
             if (bi + 2 < NB) issue(bi + 2);
 
-            // The walk enters a half of the chunk (its first block, or with 256 rows the first block of
-            // the other half): the rows of that half take the inter-chunk product from the state as it
-            // stands, which sits one token before the half (causal) or one after it (anti-causal).
-            const int hb = SPLIT ? (jbb >> 1) : 0;
-            const bool mid = SPLIT && jb > 0 && jbb == (rev ? 1 : 2);
-            if (mid) {
-                // every wave has passed this block's barrier, so the reads of the chunk's first
-                // snapshot (in its first block) are over
-                write_snapshot<TPW>(sM, Macc, t0, l32, h, false);
-                __syncthreads();
-            }
-            if ((jb == 0 || mid) && hc == hb) {
+            // The walk enters the chunk: its rows take the inter-chunk product from the state as it
+            // stands, which sits one token before the chunk (causal) or one after it (anti-causal).
+            if (jb == 0) {
                 inter_product<NOP>(Oacc, sM, qf, lo.nat);
                 int lrow;   // lane % 32, kept out of the loop-invariant (and then spilled) values
                 asm volatile("v_and_b32 %0, 31, %1" : "=v"(lrow) : "v"(tid));
                 const int a = 32 * rb + lrow;
-                const int e = rev ? max(min(clen, 128 * (hb + 1)) - a, 0) : a - 128 * hb + 1;
+                const int e = rev ? max(clen - a, 0) : a + 1;
                 const float wq = __builtin_amdgcn_exp2f((float)e * l2);
 #pragma unroll
                 for (int tv = 0; tv < 4; ++tv)
@@ -1342,7 +1405,7 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int kt = 2 * jbb + half;      // 32-key tile index inside the chunk
-                const bool active = (rev ? (kt >= rb) : (kt <= rb)) && (!SPLIT || (kt >> 2) == hc);
+                const bool active = rev ? (kt >= rb) : (kt <= rb);
                 if (!active) continue;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_at(tK + half * (32 * ROWB), lo.nat[ks]);
@@ -1394,8 +1457,7 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
 
             // the rows of the next chunk replace qf while the state update and the store run
             if (jb + 1 == nblk && !last_chunk) issue_q(rev ? cc - 1 : cc + 1);
-            // (the walk's last chunk needs the update only for the snapshot between its halves)
-            if (!last_chunk || (SPLIT && (rev ? jbb >= 2 : (jbb < 2 && nblk > 2)))) {
+            if (!last_chunk) {
                 // running state = lam^n * state + (weighted Bk block)^T Cv block, n = the block's
                 // tokens (fewer than 64 only in the slot's last block, which the backward walk
                 // meets first)
@@ -1632,7 +1694,7 @@ hipError_t launch_attn_decay_C(const Geom& g, const AttnProblem& p0, const AttnP
 hipError_t launch_attn_decay(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
                              const AttnProblem& p2, int nprob, hipStream_t st)
 {
-    if (wide_chunks(g)) return launch_attn_decay_C<256>(g, p0, p1, p2, nprob, st);
+    if (wide_chunks(g)) return launch_attn_skew<true>(g, p0, p1, p2, nprob, st);
     return launch_attn_decay_C<128>(g, p0, p1, p2, nprob, st);
 }
 }  // namespace
@@ -1642,7 +1704,7 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
 {
     const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
     if (g.decay) return launch_attn_decay(g, p, p, p, 1, st);
-    if (wide_chunks(g)) return launch_attn_skew(g, p, p, p, 1, st);
+    if (wide_chunks(g)) return launch_attn_skew<false>(g, p, p, p, 1, st);
     return launch_attn_C<128>(g, p, p, p, 1, st);
 }
 
@@ -1658,7 +1720,7 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
     if (g.decay) return launch_attn_decay(g, pq, pv, pk, 3, st);
-    if (wide_chunks(g)) return launch_attn_skew(g, pq, pv, pk, 3, st);
+    if (wide_chunks(g)) return launch_attn_skew<false>(g, pq, pv, pk, 3, st);
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }
 
