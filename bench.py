@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the attention kernel (average of its forward and backward launch),
 # from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/lasp2_kernels_cfg3_hbm_traffic.txt (counters cannot be read from inside this script).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 6.109e9}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 6.461e9}
 
 
 def nominal_flops_per_token_head(d, C):
