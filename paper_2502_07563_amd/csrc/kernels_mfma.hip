@@ -388,12 +388,14 @@ __device__ __forceinline__ void store_out_rows(const f32x16 (&Oacc)[4], char* st
                 u32x2 pk = {pack2(o[4 * q], o[4 * q + 1]), pack2(o[4 * q + 2], o[4 * q + 3])};
                 *reinterpret_cast<u32x2*>(wr + (((4 * tvv + q) ^ sw) << 4)) = pk;
             }
+        // the four reads first (they need no predicate), so that they share one wait
+        u32x4 v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(rd + 1024 * i);
+        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rd + 1024 * i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
             if (row + 8 * i < nrows)   // written once, read by a later kernel: non-temporal
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gp + (size_t)(8 * i) * ROWB + 128 * hv));
-        }
+                __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4*>(gp + (size_t)(8 * i) * ROWB + 128 * hv));
     }
 }
 
