@@ -96,6 +96,54 @@ def test_packed_documents(oracle, dtype, d, C, L):
     _run_all(oracle, 1, 2, int(cu[-1]), d, C, L, dtype, seed=40, cu=cu)
 
 
+@pytest.mark.parametrize("decay", [False, True])
+def test_slot_lengths_around_block_and_half_boundaries(oracle, decay):
+    """One slot per document, lengths on both sides of every 64-token block boundary of the 256-row
+    tiling (and of its 128-row halves) up to three chunks; each document's outputs and gradients are
+    compared on their own, so that a short document cannot hide behind a long one.  The kernel walks
+    every chunk as four blocks: the ones past a slot's end are zeroed, not loaded, and with decay the
+    backward walk meets them first."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    from paper_2502_07563_amd import synth
+
+    lens = [129, 130, 191, 192, 193, 255, 256, 257, 319, 320, 321, 383, 384, 385, 447, 448, 449,
+            511, 512, 513, 575, 577, 640, 641, 705, 767, 768]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    B, H, N, d, C, L, dtype = 1, 2, int(cu[-1]), 128, 256, 1024, "bf16"
+    lam = np.array([1.0 - 2.0 ** -6, 0.9], dtype=np.float32) if decay else None
+    x = host_inputs(47, B * H, N, d, dtype)
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu, decay=lam) if decay else bd.Problem(B, H, N, d, C, L, dtype, cu)
+    assert bd.lasp2_num_slots(p) == len(lens)
+    Q, K, V, dO = (to_device(x[n], B, H, dtype) for n in ("Q", "K", "V", "dO"))
+    M = bd.alloc_states(p)
+    P = torch.empty_like(M)
+    O, dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(4))
+    bd.lasp2_chunk_states(p, K, V, M)
+    bd.lasp2_state_prefix(p, M, P, False)
+    bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, torch.empty_like(M))
+    torch.cuda.synchronize()
+    x64 = {k: v.astype(np.float64) for k, v in x.items()}
+    if decay:
+        lam_g = np.tile(lam.astype(np.float64), B)
+        refs = (oracle.fwd_def_decay(x64["Q"], x64["K"], x64["V"], lam_g, cu),
+                *oracle.bwd_def_decay(x64["Q"], x64["K"], x64["V"], x64["dO"], lam_g, cu))
+    else:
+        refs = (oracle.fwd_def(x64["Q"], x64["K"], x64["V"], cu),
+                *oracle.bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu))
+    worst = {}
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
+        got = to_host(got)
+        assert np.isfinite(got).all(), name
+        for i, n in enumerate(lens):
+            a, b = int(cu[i]), int(cu[i + 1])
+            e = rel_l2(got[:, a:b], ref[:, a:b])
+            worst[name] = max(worst.get(name, 0.0), e)
+            assert e <= TOL[dtype], (name, n, e)
+    print({k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
 def test_prefix_in_place_and_deterministic(oracle):
     import torch
     from paper_2502_07563_amd import binding as bd
