@@ -93,6 +93,16 @@ def test_packed_documents(oracle, dtype, d, C, L):
     _run(oracle, 1, 3, 1536, d, C, L, dtype, seed=120, cu=cu)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_bf16_d128(oracle, seed):
+    """Seeded random sizes (the draws of tests/test_gpu_parity.py) with decay; one batch row, since the
+    decayed oracle is the slow one."""
+    from tests.test_gpu_parity import _random_case
+    _, H, N, C, L, cu = _random_case(50 + seed)
+    print((H, N, C, L, None if cu is None else cu.tolist()), flush=True)
+    _run(oracle, 1, H, N, 128, C, L, "bf16", seed=300 + seed, cu=cu)
+
+
 def test_all_ones_decay_is_bit_identical_to_no_decay(oracle):
     import torch
     from paper_2502_07563_amd import binding as bd

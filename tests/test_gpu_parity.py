@@ -144,6 +144,28 @@ def test_slot_lengths_around_block_and_half_boundaries(oracle, decay):
     print({k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
 
 
+def _random_case(seed):
+    """A seeded draw of sizes for the bf16, d = 128 path: sequence length, chunk length, slot length,
+    heads, and optionally a packing into documents."""
+    rng = np.random.default_rng(1000 + seed)
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    N = int(rng.choice([rng.integers(1, 300), rng.integers(300, 1200), rng.integers(1200, 2500)]))
+    C = int(rng.choice([32, 64, 128, 256, 512]))
+    L = int(rng.choice([0, C, 2 * C, 4 * C, 8 * C]))
+    cu = None
+    if B == 1 and N > 8 and rng.integers(0, 2):
+        cuts = np.sort(rng.choice(np.arange(1, N), size=int(rng.integers(1, 7)), replace=False))
+        cu = np.concatenate([[0], cuts, [N]]).astype(np.int32)
+    return B, H, N, C, L, cu
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_bf16_d128(oracle, seed):
+    B, H, N, C, L, cu = _random_case(seed)
+    print((B, H, N, C, L, None if cu is None else cu.tolist()), flush=True)
+    _run_all(oracle, B, H, N, 128, C, L, "bf16", seed=200 + seed, cu=cu)
+
+
 def test_prefix_in_place_and_deterministic(oracle):
     import torch
     from paper_2502_07563_amd import binding as bd
