@@ -25,10 +25,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
-# HBM bytes per launch of the attention kernel (average of its forward and backward launch),
-# from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/lasp2_kernels_cfg3_hbm_traffic.txt (counters cannot be read from inside this script).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 6.461e9}
+# Figures that only a counter run can give, copied from the rocprofv3 summaries under profiles/
+# (counters cannot be read from inside this script).  tests/test_bench_cli.py parses those
+# summaries and fails when a literal here differs from them.
+#   traffic_*_bytes: HBM bytes per launch of the attention kernel, FETCH_SIZE + WRITE_SIZE
+#                    (profiles/lasp2_kernels_cfg3_hbm_traffic.txt)
+#   mfma_insts_*:    v_mfma_f32_32x32x16_bf16 instructions per launch, SQ_INSTS_MFMA
+#                    (profiles/attn_skew_mfma_kernel_cfg3_sq_counters.txt)
+PROFILE_CONSTANTS = {
+    "cfg3": {"traffic_fwd_bytes": 4.363e9, "traffic_bwd_bytes": 8.560e9,
+             "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 41025536},
+}
+MFMA_FLOP = 2 * 32 * 32 * 16    # one v_mfma_f32_32x32x16_bf16
 
 
 def nominal_flops_per_token_head(d, C):
@@ -200,27 +208,49 @@ def main():
     P = bd.alloc_states(p)
     ws = bd.alloc_states(p)
     T_s = P.shape[2]
+    # One slot per sequence (e.g. --slot-len N): the serial-carry schedule.  Every prefix is zero, so
+    # the step makes no chunk_states / state_prefix call and hands P = NULL to both attention calls.
+    lone = T_s == (1 if cu is None else len(cu) - 1)
+    bwd_runs_states = lone and dtype == "bf16" and d == 128 and not args.decay
+    seg_names = ["attn_fwd", "attn_bwd"] if lone else ["chunk_states", "state_prefix", "attn_fwd", "attn_bwd"]
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
 
     def step(record):
+        e = [ev() for _ in range(len(seg_names) + 1)] if record else None
+        i = 0
+
+        def mark():
+            nonlocal i
+            if record:
+                e[i].record()
+                i += 1
+        mark()
+        if not lone:
+            bd.lasp2_chunk_states(p, K, V, P)
+            mark()
+            bd.lasp2_state_prefix(p, P, P, False)
+            mark()
+        bd.lasp2_attn_fwd(p, Q, K, V, None if lone else P, O)
+        mark()
+        bd.lasp2_attn_bwd(p, Q, K, V, dO, None if lone else P, dQ, dK, dV, ws)
+        mark()
         if record:
-            e = [ev() for _ in range(5)]
-            e[0].record()
-        bd.lasp2_chunk_states(p, K, V, P)
-        if record:
-            e[1].record()
-        bd.lasp2_state_prefix(p, P, P, False)
-        if record:
-            e[2].record()
-        bd.lasp2_attn_fwd(p, Q, K, V, P, O)
-        if record:
-            e[3].record()
-        bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
-        if record:
-            e[4].record()
             marks.append(e)
+
+    states_ms = 0.0
+    if bwd_runs_states:
+        # what lasp2_attn_bwd spends on the slots' own dM_t before its attention launch
+        bd.lasp2_chunk_states(p, Q, dO, ws)
+        torch.cuda.synchronize()
+        c0, c1 = ev(), ev()
+        c0.record()
+        for _ in range(5):
+            bd.lasp2_chunk_states(p, Q, dO, ws)
+        c1.record()
+        torch.cuda.synchronize()
+        states_ms = c0.elapsed_time(c1) / 5
 
     # A plain 1 GiB device-to-device copy, outside the timed region: what a streaming kernel
     # reaches on this device next to the published peak (and, under a counter run, a kernel
@@ -250,26 +280,50 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     tokens = B * N
     value = tokens / (dt / args.steps)
-    seg = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / len(marks) for i in range(4)]
+    nseg = len(seg_names)
+    per_step = [[m[i].elapsed_time(m[i + 1]) for m in marks] for i in range(nseg)]
+    stat = lambda v: {"mean": sum(v) / len(v), "median": sorted(v)[len(v) // 2], "min": min(v)}
+    seg = {n: stat(v) for n, v in zip(seg_names, per_step)}
 
     esz = 2 if dtype == "bf16" else 4
     # Dominant kernel: the fused attention pass, launched twice per step.  Algorithmic bytes:
     #   forward launch : Q, K, V read, O written, one state array read            (4 passes)
     #   backward launch: Q, K, V, dO read once, dQ, dK, dV written, P read once and the suffix
     #                    states twice (dV and dK each read them)                   (7 passes)
+    # With one slot per sequence no prefix state is read (forward: none; backward: the slots' own
+    # dM_t twice).
     tensor = B * H * N * d * esz
     states = B * H * T_s * d * d * 4
-    bytes_fwd = 4 * tensor + states
-    bytes_bwd = 7 * tensor + 3 * states
+    bytes_fwd = 4 * tensor + (0 if lone else states)
+    bytes_bwd = 7 * tensor + (2 if lone else 3) * states
     # HIP events bracket the forward launch exactly.  The backward launch sits inside
-    # lasp2_attn_bwd behind a states kernel and a prefix kernel that are the same launches as
-    # the step's chunk_states / state_prefix segments, so its time is attn_bwd minus those two.
-    t_fwd = seg[2]
-    t_bwd = seg[3] - seg[0] - seg[1]
-    avg_ms = 0.5 * (t_fwd + t_bwd)
-    achieved = 0.5 * (bytes_fwd + bytes_bwd) / (avg_ms * 1e-3) / 1e9
+    # lasp2_attn_bwd behind a states kernel and a combine kernel that are the same launches as
+    # the step's chunk_states / state_prefix segments (timed once before the loop when the step
+    # itself has none), so its time is attn_bwd minus those.
+    if lone:
+        pre = [states_ms if bwd_runs_states else 0.0] * len(marks)
+    else:
+        pre = [a + b for a, b in zip(per_step[0], per_step[1])]
+    fwd_v = per_step[seg_names.index("attn_fwd")]
+    bwd_v = [t - q for t, q in zip(per_step[seg_names.index("attn_bwd")], pre)]
+    mfma_path = dtype == "bf16" and d == 128
+    kern = ("attn_generic_kernel" if not mfma_path else
+            ("attn_skew_mfma_kernel" if (L or C) > 128 else ("attn_decay_mfma_kernel<128>" if args.decay else "attn_mfma_kernel<128>")))
+    if args.decay and mfma_path and (L or C) > 128:
+        kern += "<decay>"
+    consts = {} if (args.decay or args.slot_len is not None) else PROFILE_CONSTANTS.get(args.workload, {})
+
+    def launch(v, nbytes, traffic):
+        st = stat(v)
+        gbps = nbytes / (st["mean"] * 1e-3) / 1e9
+        return {"ms": st["mean"], "ms_median": st["median"], "ms_min": st["min"], "algorithmic_bytes": nbytes,
+                "GBps": gbps, "frac": gbps / HBM_PEAK_GBS, "traffic": traffic}
+    lf = launch(fwd_v, bytes_fwd, consts.get("traffic_fwd_bytes"))
+    lb = launch(bwd_v, bytes_bwd, consts.get("traffic_bwd_bytes"))
+    # the headline is the longer launch's own figure, not a blend of the two
+    head, which = (lb, "backward launch (the dQ, dV, dK problems of every slot in one launch)") \
+        if lb["ms"] >= lf["ms"] else (lf, "forward launch")
     flops_nominal = nominal_flops_per_token_head(d, C) * tokens * H
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
     out = {
         "metric": "fwd+bwd tokens/s per layer",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -277,20 +331,24 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={B} H={H} N={N} d={d} C={C} L={L or C}"
                                + (f" packed {cfg['n_docs']} docs" if cu is not None else "")
-                               + (" decay 1-2^(-5-h)" if args.decay else ""),
+                               + (" decay 1-2^(-5-h)" if args.decay else "")
+                               + (" serial carry: one slot per sequence, no state arrays in the forward" if lone else ""),
                    "state_slots": int(T_s)},
-        "ms": {"chunk_states": seg[0], "state_prefix": seg[1], "attn_fwd": seg[2], "attn_bwd": seg[3]},
+        "ms": {n: seg[n]["mean"] for n in seg_names},
+        "ms_median": {n: seg[n]["median"] for n in seg_names},
+        "ms_min": {n: seg[n]["min"] for n in seg_names},
         "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
-        "roofline": {"bound": "hbm", "kernel": "attn_skew_mfma_kernel, average of its two launches per step",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "avg_launch_ms": avg_ms, "fwd_launch_ms": t_fwd, "bwd_launch_ms": t_bwd,
-                     "fwd_launch_GBps": bytes_fwd / (t_fwd * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": f"{kern}, {which}: the longer of its two launches per step",
+                     "achieved": head["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head["frac"], "traffic": head["traffic"],
+                     "launch_ms": head["ms"], "launches": {"fwd": lf, "bwd": lb},
                      "device_copy_GBps": copy_gbps},
     }
-    if args.decay:
-        out["roofline"]["kernel"] = "attn_skew_mfma_kernel<decay>, average of its two launches per step"
-        out["roofline"]["traffic"] = None
+    if "mfma_insts_fwd" in consts:
+        # executed matrix-core work: the attention launches from the SQ_INSTS_MFMA counter, the two
+        # chunk-state launches from their tiling (2 d^2 flop per token and head, no padding at this size)
+        executed = (consts["mfma_insts_fwd"] + consts["mfma_insts_bwd"]) * MFMA_FLOP + 2 * 2.0 * d * d * tokens * H
+        out["mfma_frac_executed"] = executed / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if not args.no_cpu_baseline and not args.decay:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
     print(json.dumps(out))

@@ -17,12 +17,22 @@
  * (suffix) combine dM_{t+1:T}.
  *
  * Two granularities (the result depends on neither):
- *   C  chunk length: the side of the masked quadratic block and the period at
- *      which the inter-chunk state operand is refreshed inside a kernel;
+ *   C  chunk length: in the plain fp32 kernels the side of the masked quadratic
+ *      block and the period at which the inter-chunk state operand is
+ *      refreshed.  The matrix-core kernels (bf16, d = 128) tile a slot in
+ *      blocks of their own (256 rows, masked products over 128-row halves;
+ *      128 rows when no slot is longer) whatever C is: there C only fixes the
+ *      slots through L;
  *   L  tokens per state slot, a multiple of C (0 means L = C, the paper-literal
  *      layout with one state per chunk).  One slot is what one sequence-
  *      parallel rank would own; its chunks are walked by one workgroup that
  *      carries the running state on chip.
+ *   L >= the longest sequence (document) makes every sequence a single slot:
+ *   the serial-carry schedule of LASP-1 on one device (Sec. "LASP-1 vs
+ *   LASP-2"; appendix Algorithm "LASP-1 w/ Masking"), one pass that carries M
+ *   from chunk to chunk with no state array at all.  Every prefix is then
+ *   zero, lasp2_attn_fwd and lasp2_attn_bwd accept P = NULL, and
+ *   lasp2_chunk_states / lasp2_state_prefix need not be called.
  *
  * Slots.  Unpacked input: every (b,h) row of N tokens has T_s = ceil(N/L)
  * slots, slot s = tokens [s*L, min(N,(s+1)*L)).  Packed input (B must be 1):
@@ -41,16 +51,27 @@
  * the slot lengths, P_t = lam^(n_{t-1}) P_{t-1} + M_{t-1}; the token at local
  * index a of a chunk reads the state before the chunk with weight lam^(a+1).
  * The backward mirrors this with states anchored at the slots' first tokens.
- * lam = 1 for every head gives exactly the undecayed path.  Decay is given by
+ * lam = 1 for every head computes the undecayed result (bit for bit on the
+ * plain kernels; on the matrix cores within rounding, because the decayed
+ * backward walks each slot in the opposite direction).  Decay is given by
  * the two `decay_*` pointers of the descriptor (both NULL: none).
+ * Precision with decay on the matrix cores (bf16, d = 128, every factor
+ * >= 0.35; a smaller factor sends the whole call to the plain fp32 kernels,
+ * because lam^63 must stay inside the bf16 / fp32 exponent range): the rows
+ * that enter a state product are weighted first and rounded to bf16 like every
+ * matrix-core operand, so the states lasp2_chunk_states returns carry that
+ * rounding (relative error 3e-4 .. 1e-3, against < 1e-6 without decay, where
+ * the products of bf16 inputs are exact); O, dQ, dK, dV keep the bf16 bound.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers, 16-byte aligned, contiguous,
  *     d fastest: Q,K,V,O,dO,dQ,dK,dV are [B,H,N,d] in `dtype` (fp32 or bf16);
  *     states M,P and the workspace are fp32, [B,H,T_s,d,d] with M[a][b] =
  *     sum_tokens k[a]*v[b].
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls and is re-entrant.
+ *   - The caller owns every buffer.  The library allocates nothing and is
+ *     re-entrant.  Between calls it keeps only per-device facts about the
+ *     hardware (number of compute units; which kernels have had their LDS
+ *     limit raised), never anything about a problem.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls only enqueue work; outputs are valid once the stream has been
  *     synchronised.  The descriptor and `cu_seqlens_host` are read during the
@@ -61,11 +82,12 @@
  *     the device.  Nothing aborts or throws.
  *   - B, H or N equal to 0 is a valid empty problem: the call returns LASP2_OK
  *     and launches nothing (pointers are then not examined).
- *   - Supported: d in {16, 32, 64, 128}; 1 <= C <= 512.  The MFMA kernels
- *     cover bf16 with d = 128 for every C (they tile a slot in chunks of
- *     their own, which the result does not depend on) without decay; any
- *     other supported combination runs the plain fp32-FMA kernels.  There is
- *     no CPU fallback.
+ *   - Supported: d in {16, 32, 64, 128}; 1 <= C <= 512; B*H <= 65535 (the
+ *     plain kernels carry the group index in the grid's second dimension).
+ *     The MFMA kernels cover bf16 with d = 128 for every C, with and without
+ *     decay (with decay: every factor >= 0.35, see above); any other
+ *     supported combination runs the plain fp32-FMA kernels.  There is no CPU
+ *     fallback.
  */
 #ifndef LASP2_H
 #define LASP2_H
@@ -146,6 +168,9 @@ int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P,
  * where M_{1:t-1} = P[slot] + the states of the slot's earlier chunks (carried
  * on chip).  In: Q,K,V [B,H,N,d]; P [B,H,T_s,d,d] fp32 from lasp2_state_prefix
  * (reverse = 0).  Out: O [B,H,N,d] in `dtype`, written once.
+ * P may be NULL when every sequence (document) is a single slot: its prefix is
+ * zero, the slot starts from a zero state (serial-carry schedule).  With more
+ * than one slot in some sequence a NULL P is LASP2_ERR_NULL.
  */
 int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                    const void* V, const float* P, void* O, void* stream);
@@ -161,6 +186,11 @@ int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K,
  * `workspace`: device scratch of at least lasp2_workspace_size() bytes,
  * 16-byte aligned; its contents on return are unspecified (suffix states in
  * the form the kernels that ran wanted them).
+ * When every sequence (document) is a single slot, all prefixes and suffixes
+ * are zero: P is not read and may be NULL, and the combine is skipped.  The
+ * plain kernels and the decayed matrix-core kernels then need no workspace
+ * either (NULL / 0 bytes accepted); the undecayed matrix-core kernels still
+ * use it for the slots' own dM_t, from which their forward walk subtracts.
  */
 int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                    const void* V, const void* dO, const float* P,

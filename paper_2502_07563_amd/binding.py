@@ -12,7 +12,9 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "liblasp2.so")
+# LASP2_LIB_PATH names another build of the same library (e.g. the -DLASP2_FULL_WAITS checking
+# variant, see build.py); there is still no fallback: the named file must exist.
+LIB_PATH = os.environ.get("LASP2_LIB_PATH") or os.path.join(_PKG, "liblasp2.so")
 
 LASP2_F32, LASP2_BF16 = 0, 1
 STATUS = {0: "LASP2_OK", -1: "LASP2_ERR_NULL", -2: "LASP2_ERR_SHAPE", -3: "LASP2_ERR_DTYPE",

@@ -82,11 +82,12 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(
     int tok0, len;
     slot_range(g, s, tok0, len);
     const size_t gbase = (size_t)grp * (size_t)g.N * D;
-    const float* st0 = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+    // state == NULL: every slot opens its document, so the prefix (suffix) it starts from is zero
+    const float* st0 = state ? state + ((size_t)grp * g.T_s + s) * (size_t)(D * D) : nullptr;
 
     for (int e = tid; e < D * D; e += kThreads) {
         int a = e / D, b = e % D;
-        Mst[e] = transpose_state ? st0[b * D + a] : st0[e];
+        Mst[e] = st0 ? (transpose_state ? st0[b * D + a] : st0[e]) : 0.f;
     }
     __syncthreads();
 
@@ -300,8 +301,7 @@ hipError_t rows_state_generic_TD(const Geom& g, const T* A, const float* state, 
     constexpr size_t smem = sizeof(float) * ((size_t)D * D + (size_t)kProjRows * (kThreads / D) * D);
     auto kern = rows_state_generic_kernel<T, D>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = allow_dynamic_lds<rows_state_generic_kernel<T, D>>((int)smem);
         if (e != hipSuccess) return e;
     }
     dim3 grid(g.T_s, g.G), block(kThreads);
@@ -609,8 +609,7 @@ hipError_t attn_generic_TD(const Geom& g, const T* A, const T* Bk, const T* Cv, 
     size_t smem = sizeof(float) * ((size_t)D * D + (size_t)kRows * (D + 1) + (size_t)kRows * (g.C + 1));
     auto kern = attn_generic_kernel<T, D>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = allow_dynamic_lds<attn_generic_kernel<T, D>>((int)smem);
         if (e != hipSuccess) return e;
     }
     dim3 grid(g.T_s, g.G), block(kThreads);

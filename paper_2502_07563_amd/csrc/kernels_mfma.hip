@@ -467,7 +467,11 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 
     // running state tiles, C/D layout: rows = d_k (first index), columns = d_v
     f32x16 Macc[TPW];
-    {
+#pragma unroll
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
+    if (state) {   // NULL: every slot opens its document and starts from a zero state
         const float* st = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
         const float sg = anti ? -1.f : 1.f;
 #pragma unroll
@@ -770,7 +774,11 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     // running state tiles, C/D layout: rows = d_k (first index), columns = d_v; the anti-causal
     // walk keeps minus the inclusive suffix and adds the blocks it passes (see attn_mfma_kernel)
     f32x16 Macc[TPW];
-    {
+#pragma unroll
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
+    if (pr.state) {   // NULL: every slot opens its document and starts from a zero state
         const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
         const float sg = ENDSTATE ? -1.f : 1.f;
 #pragma unroll
@@ -1184,8 +1192,7 @@ hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem
     // stages + snapshot + 4 KiB of output staging per wave
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + (C / 32) * 4096;
     auto kern = attn_mfma_kernel<C>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<attn_mfma_kernel<C>>(smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
@@ -1200,8 +1207,7 @@ hipError_t launch_attn_skew(const Geom& g, const AttnProblem& p0, const AttnProb
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 8 * 4096;
     auto kern = attn_skew_mfma_kernel<DECAY>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<attn_skew_mfma_kernel<DECAY>>(smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
@@ -1288,7 +1294,11 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
 
     // running state tiles, C/D layout: rows = d_k (first index), columns = d_v
     f32x16 Macc[TPW];
-    {
+#pragma unroll
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
+    if (pr.state) {   // NULL: every slot opens its document and starts from a zero state
         const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
@@ -1655,19 +1665,11 @@ hipError_t launch_states_mfma(const Geom& g, const void* K, const void* V, float
 {
     constexpr int smem = 2 * ST_NST * ST_STAGE;   // 80 KiB: two workgroups per CU
     auto kern = g.decay ? states_mfma_kernel<true> : states_mfma_kernel<false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = g.decay ? allow_dynamic_lds<states_mfma_kernel<true>>(smem)
+                           : allow_dynamic_lds<states_mfma_kernel<false>>(smem);
     if (e != hipSuccess) return e;
     // two workgroups per CU, each walking through its share of the slots
-    static int cu_count[64] = {};   // per device ordinal, filled on first use (same value from any thread)
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
-    if (dev >= 0) cus = cu_count[dev];
-    if (cus <= 0) {
-        if (dev < 0 || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-        if (dev >= 0) cu_count[dev] = cus;
-    }
+    const int cus = cu_count();
     const long long nunits = (long long)g.T_s * g.G;
     if (nunits == 0) return hipSuccess;
     dim3 grid((unsigned)std::min<long long>(nunits, 2LL * cus)), block(ST_NT);
@@ -1683,8 +1685,7 @@ hipError_t launch_attn_decay_C(const Geom& g, const AttnProblem& p0, const AttnP
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + (C / 32) * 4096;
     auto kern = attn_decay_mfma_kernel<C>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<attn_decay_mfma_kernel<C>>(smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)nprob * ((units + 7u) & ~7u);
@@ -1734,8 +1735,7 @@ hipError_t launch_rows_state_mfma(const Geom& g, const RowsStateProblem* probs, 
         const RowsStateProblem& p = probs[i < n ? i : 0];
         a[i] = RowsStateArgs{static_cast<const char*>(p.A), p.state, static_cast<char*>(p.out), p.transpose_state};
     }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rows_state_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<rows_state_mfma_kernel>(smem);
     if (e != hipSuccess) return e;
     const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
     const unsigned gx = (unsigned)n * ((units + 7u) & ~7u);

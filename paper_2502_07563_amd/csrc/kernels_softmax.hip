@@ -527,10 +527,14 @@ __global__ __launch_bounds__(SM_NW * 64) void softmax_bwd_dq_mfma_kernel(
 // =====================================================================================
 constexpr int SK_NW = 4, SK_KB = SK_NW * 32;
 
+// four bytes per lane, otherwise as dma16 (M0 is written and named as clobbered)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma4(const char* sbase, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 __global__ __launch_bounds__(SK_NW * 64) void softmax_bwd_dkv_mfma_kernel(
     Geom g, const char* __restrict__ Q, const char* __restrict__ K, const char* __restrict__ V,
@@ -830,8 +834,7 @@ hipError_t launch_softmax_bwd_dkv_mfma(const Geom& g, const void* Q, const void*
                                        void* dV, int causal, hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + NSTAGE * 512;   // 97.5 KiB
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_bwd_dkv_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<softmax_bwd_dkv_mfma_kernel>(smem);
     if (e != hipSuccess) return e;
     const unsigned nkb = ((unsigned)g.N + SK_KB - 1) / SK_KB;
     const unsigned units = (unsigned)g.G * nkb;
@@ -850,8 +853,7 @@ hipError_t launch_softmax_bwd_dq_mfma(const Geom& g, const void* Q, const void* 
                                       int causal, hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + SM_NW * 4096;   // 128 KiB
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_bwd_dq_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<softmax_bwd_dq_mfma_kernel>(smem);
     if (e != hipSuccess) return e;
     if (g.qn == 0) return hipSuccess;
     const unsigned nqb = ((unsigned)g.qn + SM_QB - 1) / SM_QB;
@@ -869,8 +871,7 @@ hipError_t launch_softmax_fwd_mfma(const Geom& g, const void* Q, const void* K, 
                                    float* LSE, int causal, hipStream_t st)
 {
     constexpr int smem = 2 * NSTAGE * STAGE_BYTES + SM_NW * 4096;   // 128 KiB
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_fwd_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = allow_dynamic_lds<softmax_fwd_mfma_kernel>(smem);
     if (e != hipSuccess) return e;
     if (g.qn == 0) return hipSuccess;
     const unsigned nqb = ((unsigned)g.qn + SM_QB - 1) / SM_QB;

@@ -80,6 +80,7 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     g->L = L;
     g->T_s = (int32_t)T_s;
     g->n_seqs = desc->n_seqs;
+    g->lone_slots = (T_s == (desc->n_seqs > 0 ? (int64_t)desc->n_seqs : (int64_t)1)) ? 1 : 0;
     g->cu = desc->cu_seqlens_dev;
     *empty = (G == 0 || desc->N == 0);
     return LASP2_OK;
@@ -167,7 +168,9 @@ int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
     if (empty) return LASP2_OK;
-    rc = check_ptrs({Q, K, V, P, O});
+    // Serial-carry schedule: when every document is one slot, each slot starts from a zero state
+    // and P may be left out (NULL); the states and prefix calls are then not needed at all.
+    rc = (P == nullptr && g.lone_slots) ? check_ptrs({Q, K, V, O}) : check_ptrs({Q, K, V, P, O});
     if (rc != LASP2_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (mfma_path_supported(g, desc->dtype)) return from_hip(launch_attn_fwd_mfma(g, Q, K, V, P, O, st));
@@ -183,21 +186,38 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
     if (empty) return LASP2_OK;
-    rc = check_ptrs({Q, K, V, dO, P, dQ, dK, dV, workspace});
+    const bool fast = mfma_path_supported(g, desc->dtype);
+    // Which suffix states the kernels want: the plain kernels and the MFMA kernels with decay walk
+    // each slot backwards from the EXCLUSIVE suffix; the MFMA kernels without decay walk forwards
+    // from the INCLUSIVE suffix and subtract (see attn_mfma_kernel), which lets the three
+    // problems of a slot share their reads.
+    const bool inclusive = fast && !g.decay;
+    // Every document a single slot (serial-carry schedule): all exclusive prefixes and suffixes are
+    // zero.  P is then not read (and may be NULL), kernels that start from the exclusive suffix need
+    // neither states nor workspace, and the inclusive suffix of a lone slot is its own state, so
+    // the combine is skipped.
+    const bool lone = g.lone_slots != 0;
+    const bool need_states = !lone || inclusive;
+    if ((!lone && !P) || (need_states && !workspace)) return LASP2_ERR_NULL;   // NULL before alignment, as everywhere
+    rc = check_ptrs({Q, K, V, dO, dQ, dK, dV});
     if (rc != LASP2_OK) return rc;
+    if ((!lone && !aligned16(P)) || (need_states && !aligned16(workspace))) return LASP2_ERR_ALIGN;
     size_t need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
-    if (workspace_bytes < need) return LASP2_ERR_WORKSPACE;
+    if (need_states && workspace_bytes < need) return LASP2_ERR_WORKSPACE;
+    if (lone) P = nullptr;
 
     hipStream_t st = (hipStream_t)stream;
-    float* dR = static_cast<float*>(workspace);
-    const bool fast = mfma_path_supported(g, desc->dtype);
-    // dM_t = Q_t^T dO_t per slot, then its suffix combine in place: exclusive for the plain
-    // kernels (which walk each slot backwards), inclusive for the MFMA kernels (which walk
-    // forwards and subtract, see attn_mfma_kernel).
-    hipError_t e = run_states(g, desc->dtype, Q, dO, dR, 1, st);
-    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    e = launch_state_prefix(g, dR, dR, 1, (fast && !g.decay) ? 1 : 0, st);
-    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    float* dR = need_states ? static_cast<float*>(workspace) : nullptr;
+    hipError_t e = hipSuccess;
+    if (need_states) {
+        // dM_t = Q_t^T dO_t per slot, then its suffix combine in place
+        e = run_states(g, desc->dtype, Q, dO, dR, 1, st);
+        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    }
+    if (!lone) {
+        e = launch_state_prefix(g, dR, dR, 1, inclusive ? 1 : 0, st);
+        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    }
     if (fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
     // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.

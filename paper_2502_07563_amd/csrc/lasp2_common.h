@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "lasp2.h"
 
 namespace lasp2 {
@@ -18,6 +20,8 @@ struct Geom {
     int64_t L;            // tokens per state slot (multiple of C)
     int32_t T_s;          // slots per group
     int32_t n_seqs;       // packed: number of documents; 0 = not packed
+    int32_t lone_slots;   // host decision: every document (sequence) is a single slot, so every
+                          // exclusive prefix and suffix state is zero
     const int32_t* cu;    // packed: DEVICE pointer to n_seqs+1 offsets
     int32_t H;            // heads (group g uses decay[g % H])
     const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
@@ -63,6 +67,50 @@ __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int&
         }
         base += ns;
     }
+}
+
+// Device ordinal of the calling thread's current device, or -1 when it cannot serve as an index
+// into the small per-device caches below.
+constexpr int kMaxDevices = 64;
+inline int current_device_index()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+
+// Raises the dynamic-LDS limit of kernel Kern to `bytes` on the current device.  The runtime
+// call is made once per kernel and device (and again only for a larger request), not at every
+// launch: what was granted is remembered in a per-kernel array of atomics.  These caches, and
+// cu_count() below, are the only things the library keeps between calls; they hold properties
+// of the device, never of a problem.
+template <auto Kern>
+hipError_t allow_dynamic_lds(int bytes)
+{
+    static std::atomic<int> granted[kMaxDevices] = {};
+    const int dev = current_device_index();
+    if (dev >= 0 && granted[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    if (dev >= 0) {
+        int seen = granted[dev].load(std::memory_order_relaxed);
+        while (seen < bytes && !granted[dev].compare_exchange_weak(seen, bytes, std::memory_order_release)) {}
+    }
+    return hipSuccess;
+}
+
+// Compute units of the current device (asked once per device; 256 if the query fails).
+inline int cu_count()
+{
+    static std::atomic<int> cached[kMaxDevices] = {};
+    const int dev = current_device_index();
+    int cus = dev >= 0 ? cached[dev].load(std::memory_order_relaxed) : 0;
+    if (cus > 0) return cus;
+    if (dev < 0 || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    if (dev >= 0) cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
 }
 
 // ---- launchers implemented in the kernel files (return hipGetLastError()) ----

@@ -125,17 +125,22 @@ __device__ __forceinline__ uint32_t lds_addr_of(const char* p)
 
 // One wave instruction of direct global->LDS load: lane l fetches the 16 bytes at sbase + voff
 // (sbase and lds_base uniform, held in scalar registers; voff per lane) into LDS at
-// lds_base + 16 l.
+// lds_base + 16 l.  The statement writes M0 and says so in its clobber list, so that the
+// compiler never carries a value of its own in M0 across it; the compiler reserves M0 and
+// remarks on any clobber of a reserved register, which is silenced for these statements only.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
 // The same load marked non-temporal, for data that is read exactly once.
 __device__ __forceinline__ void dma16_nt(const char* sbase, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // Byte offset, inside a block of rows that starts at a multiple of 16, of the 16 bytes that lane
 // `lane` of wave instruction `k` (rows 4k .. 4k+3) must fetch so that they land swizzled.
@@ -190,10 +195,20 @@ __device__ __forceinline__ void zero_tail_rows(int tok, int len, char* tx, char*
     }
 }
 
+// Counted waits.  Built with -DLASP2_FULL_WAITS every one of them waits for ALL outstanding
+// vector-memory operations instead (vmcnt(0)): slower, but free of any assumption about how many
+// younger operations are in flight.  A result that differs between the two builds points at a
+// miscounted wait; one that does not, at something else.
+#ifdef LASP2_FULL_WAITS
+#define LASP2_WAIT_COUNT(n) 0
+#else
+#define LASP2_WAIT_COUNT(n) (n)
+#endif
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LASP2_WAIT_COUNT(N)) : "memory");
 }
 
 // Global loads whose completion the kernel tracks itself.  The compiler knows nothing of them, so
@@ -211,7 +226,7 @@ template <int N>
 __device__ __forceinline__ uint32_t wait_vmcnt_token()
 {
     uint32_t zero;
-    asm volatile("s_waitcnt vmcnt(%1)\n\tv_mov_b32 %0, 0" : "=v"(zero) : "n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%1)\n\tv_mov_b32 %0, 0" : "=v"(zero) : "n"(LASP2_WAIT_COUNT(N)) : "memory");
     return zero;
 }
 

@@ -23,3 +23,28 @@ def test_nominal_flop_count():
     d, C = 128, 256
     assert bench.nominal_flops_per_token_head(d, C) == 7 * d * (C + 1) + 6 * 2 * d * d
     assert bench.HBM_PEAK_GBS == 8000.0 and bench.MFMA_BF16_PEAK_TFLOPS == 2500.0
+
+
+def _bench_module():
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    return bench
+
+
+def test_counter_figures_in_bench_match_the_committed_profile_summaries():
+    """bench.py cannot read hardware counters, so `roofline.traffic` and `mfma_frac_executed` come
+    from literals copied out of the rocprofv3 summaries under profiles/.  The literals must be the
+    numbers those summaries print."""
+    import re
+    consts = _bench_module().PROFILE_CONSTANTS["cfg3"]
+    GiB = float(1 << 30)
+    text = open(os.path.join(ROOT, "profiles", "lasp2_kernels_cfg3_hbm_traffic.txt")).read()
+    fwd = float(re.search(r"attention pass, forward launch\s*:\s*([0-9.]+) GiB moved", text).group(1))
+    bwd = float(re.search(r"attention pass, backward launch\s*:\s*([0-9.]+) GiB moved", text).group(1))
+    # the summaries print GiB with three decimals
+    assert abs(consts["traffic_fwd_bytes"] - fwd * GiB) <= 0.001 * GiB
+    assert abs(consts["traffic_bwd_bytes"] - bwd * GiB) <= 0.001 * GiB
+    text = open(os.path.join(ROOT, "profiles", "attn_skew_mfma_kernel_cfg3_sq_counters.txt")).read()
+    assert consts["mfma_insts_fwd"] == int(re.search(r"forward\s+SQ_INSTS_MFMA\s+(\d+)", text).group(1))
+    assert consts["mfma_insts_bwd"] == int(re.search(r"backward\s+SQ_INSTS_MFMA\s+(\d+)", text).group(1))

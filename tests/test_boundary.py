@@ -146,6 +146,36 @@ def test_null_and_alignment_errors_reach_no_device():
     assert lib.lasp2_softmax_bwd_share(r, i64(8), i64(100), *([FAKE] * 10), ctypes.c_size_t(sneed.value - 1), 1, None) == -5
 
 
+def test_null_prefix_is_accepted_only_when_every_sequence_is_one_slot():
+    """Serial-carry schedule: with one slot per sequence (document) every prefix is zero and P may
+    be NULL; the call then goes on to its other checks (shown here by the misaligned pointer it
+    reports next, still before any device work).  With several slots a NULL P is an error."""
+    lib = B.lib()
+    one = ctypes.byref(_desc(N=1024, C=128, L=1024))                     # fp32: plain kernels
+    many = ctypes.byref(_desc(N=1024, C=128, L=512))
+    assert lib.lasp2_attn_fwd(one, FAKE, FAKE, FAKE, None, ODD, None) == -6
+    assert lib.lasp2_attn_fwd(many, FAKE, FAKE, FAKE, None, ODD, None) == -1
+    # backward, plain kernels: neither P nor a workspace is needed
+    assert lib.lasp2_attn_bwd(one, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ODD, None, ctypes.c_size_t(0), None) == -6
+    assert lib.lasp2_attn_bwd(many, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ODD, None, ctypes.c_size_t(0), None) == -1
+    assert lib.lasp2_attn_bwd(many, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, None, ctypes.c_size_t(0), None) == -1
+    # backward on the matrix cores without decay: the slots' own dM_t still go through the workspace
+    mf = ctypes.byref(_desc(N=1024, d=128, C=256, L=1024, dtype=B.LASP2_BF16))
+    assert lib.lasp2_attn_bwd(mf, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, ctypes.c_size_t(0), None) == -1
+    assert lib.lasp2_attn_bwd(mf, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, ctypes.c_size_t(16), None) == -5
+    assert lib.lasp2_attn_bwd(mf, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ODD, FAKE, ctypes.c_size_t(1 << 30), None) == -6
+    # ... with decay they walk backwards from zero and need none
+    lam = np.array([0.9, 1.0], dtype=np.float32)
+    md = ctypes.byref(_desc(N=1024, d=128, C=256, L=1024, dtype=B.LASP2_BF16, decay_host=lam.ctypes.data,
+                            decay_dev=0x3000))
+    assert lib.lasp2_attn_bwd(md, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ODD, None, ctypes.c_size_t(0), None) == -6
+    # packed: one slot per document
+    cu = np.array([0, 64, 300, 301, 1024], dtype=np.int32)
+    pk = lambda L: ctypes.byref(_desc(C=128, L=L, n_seqs=4, cu_seqlens_host=cu.ctypes.data, cu_seqlens_dev=0x2000))
+    assert lib.lasp2_attn_fwd(pk(768), FAKE, FAKE, FAKE, None, ODD, None) == -6      # longest document: 723 tokens
+    assert lib.lasp2_attn_fwd(pk(640), FAKE, FAKE, FAKE, None, ODD, None) == -1      # ... now two slots
+
+
 def test_decay_errors():
     lam = np.array([0.9, 1.0], dtype=np.float32)
     assert _slots(_desc(decay_host=lam.ctypes.data, decay_dev=0x3000))[0] == 0

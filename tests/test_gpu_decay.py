@@ -1,12 +1,14 @@
 """GPU parity of the masked entry points with scalar decay (mask entries lam^(i-j), one factor
-per head) against the CPU oracle's decayed definition, element by element, on seeded inputs:
+per head) against the CPU oracle's decayed definition on seeded inputs (every element enters;
+the bar is the relative L2 error of the whole tensor and its maximum over 256-row blocks):
 fp32 and bf16 storage, several chunks and slots, ragged tails, packed documents, and the
 lam = 1 case, which must reproduce the undecayed path bit for bit."""
 import numpy as np
 import pytest
 
 from paper_2502_07563_amd import synth
-from tests.util import TOL, TOL_STATE, host_inputs, rel_l2, slot_partition, to_device, to_host
+from tests.util import (TOL, TOL_STATE, assert_close_blocks, host_inputs, rel_l2, slot_partition, to_device,
+                        to_host)
 
 pytestmark = pytest.mark.gpu
 
@@ -50,18 +52,21 @@ def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None, lam=None):
                                        bounds, lam_g, first, reverse=True)
     errs["M"] = rel_l2(to_host(M), M_ref)
     errs["P"] = rel_l2(to_host(P), P_ref)
-    errs["dP"] = rel_l2(to_host(ws), dP_ref)        # the generic path leaves the exclusive suffix there
-    errs["O"] = rel_l2(to_host(O), oracle.fwd_def_decay(x64["Q"], x64["K"], x64["V"], lam_g, cu))
-    refs = oracle.bwd_def_decay(x64["Q"], x64["K"], x64["V"], x64["dO"], lam_g, cu)
-    for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs):
+    # the workspace holds the exclusive suffix afterwards, unless every document is a single slot:
+    # all suffixes are then zero and the library does not touch the workspace
+    lone = len(first) == (1 if cu is None else len(cu) - 1)
+    errs["dP"] = 0.0 if lone else rel_l2(to_host(ws), dP_ref)
+    refs = (oracle.fwd_def_decay(x64["Q"], x64["K"], x64["V"], lam_g, cu),
+            *oracle.bwd_def_decay(x64["Q"], x64["K"], x64["V"], x64["dO"], lam_g, cu))
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
         errs[name] = rel_l2(to_host(got), ref)
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     # The MFMA kernels (bf16, d = 128, every factor >= 0.35) round the weighted rows lam^e k to
     # bf16 before the product, so their states carry bf16 rounding; the plain kernels weight in fp32.
     mfma = dtype == "bf16" and d == 128 and float(lam.min()) >= 0.35
     assert max(errs["M"], errs["P"], errs["dP"]) <= (TOL["bf16"] if mfma else TOL_STATE), errs
-    for k in ("O", "dQ", "dK", "dV"):
-        assert errs[k] <= TOL[dtype], errs
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
+        assert_close_blocks(name, to_host(got), ref, TOL[dtype])
     return dict(O=O, dQ=dQ, dK=dK, dV=dV, P=P)
 
 

@@ -1,11 +1,13 @@
 """GPU parity of the entry points without masking (state total, O = Q M, and the backward)
-against the CPU oracle, element by element, on seeded inputs: fp32 and bf16, several slots,
-ragged tails, packed documents, in-place totals."""
+against the CPU oracle on seeded inputs (every element enters; the bar is the relative L2 error
+of the whole tensor and its maximum over 256-row blocks): fp32 and bf16, several slots, ragged
+tails, packed documents, in-place totals."""
 import numpy as np
 import pytest
 
 from paper_2502_07563_amd import synth
-from tests.util import TOL, TOL_STATE, host_inputs, rel_l2, slot_partition, to_device, to_host
+from tests.util import (TOL, TOL_STATE, assert_close_blocks, host_inputs, rel_l2, slot_partition, to_device,
+                        to_host)
 
 pytestmark = pytest.mark.gpu
 
@@ -39,14 +41,14 @@ def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None):
     dS_ref = oracle.state_total(oracle.chunk_states(x64["Q"], x64["dO"], bounds), first)
     errs["S"] = rel_l2(to_host(S), S_ref)
     errs["dS"] = rel_l2(to_host(ws), dS_ref)
-    errs["O"] = rel_l2(to_host(O), oracle.nomask_fwd_def(x64["Q"], x64["K"], x64["V"], cu))
-    refs = oracle.nomask_bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu)
-    for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), refs):
+    refs = (oracle.nomask_fwd_def(x64["Q"], x64["K"], x64["V"], cu),
+            *oracle.nomask_bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu))
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
         errs[name] = rel_l2(to_host(got), ref)
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert errs["S"] <= TOL_STATE and errs["dS"] <= TOL_STATE, errs
-    for k in ("O", "dQ", "dK", "dV"):
-        assert errs[k] <= TOL[dtype], errs
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
+        assert_close_blocks(name, to_host(got), ref, TOL[dtype])
     return errs
 
 

@@ -1,10 +1,14 @@
-"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element,
-on the same seeded inputs.  Sizes here are ones the brute-force oracle finishes in seconds;
-they span several chunks, several slots and ragged tails."""
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs,
+every element of every output entering the comparison.  The bar for O, dQ, dK, dV is the
+tolerance on the relative L2 error of the whole tensor AND on its maximum over blocks of 256
+consecutive rows of each (batch, head) (tests/util.py: assert_close_blocks), so that a fault
+confined to a few rows of an early chunk fails.  Sizes here are ones the brute-force oracle
+finishes in seconds; they span several chunks, several slots and ragged tails."""
 import numpy as np
 import pytest
 
-from tests.util import TOL, TOL_STATE, host_inputs, rel_l2, slot_partition, to_device, to_host
+from tests.util import (TOL, TOL_STATE, assert_close_blocks, host_inputs, rel_l2, slot_partition, to_device,
+                        to_host)
 
 pytestmark = pytest.mark.gpu
 
@@ -36,9 +40,8 @@ def _run_all(oracle, B, H, N, d, C, L, dtype, seed, cu=None, check_bwd=True):
     errs["M"] = rel_l2(to_host(M), M_ref)
     errs["P"] = rel_l2(to_host(P), P_ref)
     O_ref = oracle.fwd_def(x64["Q"], x64["K"], x64["V"], cu)
-    errs["O"] = rel_l2(to_host(O), O_ref)
     assert errs["M"] <= TOL_STATE and errs["P"] <= TOL_STATE, errs
-    assert errs["O"] <= TOL[dtype], errs
+    errs["O"], errs["O_blk"] = assert_close_blocks("O", to_host(O), O_ref, TOL[dtype])
 
     if check_bwd:
         dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
@@ -53,12 +56,9 @@ def _run_all(oracle, B, H, N, d, C, L, dtype, seed, cu=None, check_bwd=True):
         torch.cuda.synchronize()
         dP_ref = oracle.state_prefix(oracle.chunk_states(x64["Q"], x64["dO"], bounds), first, reverse=True)
         errs["dP"] = rel_l2(to_host(dP), dP_ref)
-        errs["dQ"] = rel_l2(to_host(dQ), dQ_ref)
-        errs["dK"] = rel_l2(to_host(dK), dK_ref)
-        errs["dV"] = rel_l2(to_host(dV), dV_ref)
         assert errs["dP"] <= TOL_STATE, errs
-        for k in ("dQ", "dK", "dV"):
-            assert errs[k] <= TOL[dtype], errs
+        for k, got, ref in (("dQ", dQ, dQ_ref), ("dK", dK, dK_ref), ("dV", dV, dV_ref)):
+            errs[k], errs[k + "_blk"] = assert_close_blocks(k, to_host(got), ref, TOL[dtype])
     print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     return errs
 
@@ -235,3 +235,47 @@ def test_many_slots_not_multiple_of_eight(oracle):
     """Slot counts that do not fill the last group of eight workgroups of a launch."""
     _run_all(oracle, 1, 1, 256 * 11 + 70, 128, 256, 256, "bf16", seed=71)
     _run_all(oracle, 2, 1, 256 * 3, 128, 256, 256, "bf16", seed=72)
+
+
+@pytest.mark.parametrize("dtype,d,C,N,decay", [("bf16", 128, 256, 1900, False), ("bf16", 128, 256, 1900, True),
+                                               ("bf16", 128, 64, 100, False), ("f32", 32, 64, 700, False),
+                                               ("f32", 32, 64, 700, True)])
+@pytest.mark.parametrize("packed", [False, True])
+def test_serial_carry_schedule_without_state_arrays(oracle, dtype, d, C, N, decay, packed):
+    """One slot per sequence (document): lasp2_attn_fwd and lasp2_attn_bwd with P = NULL and no
+    chunk_states / state_prefix calls at all, one pass that carries the state from chunk to chunk,
+    against the definition.  The backward gets a workspace only where the kernels still want one
+    (matrix cores without decay)."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    B, H = (1, 3) if packed else (2, 2)
+    cu = None
+    if packed:
+        lens = [N // 5, 1, N // 3, 37] if N > 200 else [N // 4, 1, N // 2, 7]
+        lens.append(N - sum(lens))
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    longest = N if cu is None else int(np.diff(cu).max())
+    L = -(-longest // C) * C
+    lam = np.array([0.97, 0.5, 1.0][:H], dtype=np.float32) if decay else None
+    p = bd.Problem(B, H, N, d, C, L, dtype, cu, decay=lam)
+    assert bd.lasp2_num_slots(p) == (1 if cu is None else len(cu) - 1)
+    x = host_inputs(75, B * H, N, d, dtype)
+    Q, K, V, dO = (to_device(x[n], B, H, dtype) for n in ("Q", "K", "V", "dO"))
+    O, dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(4))
+    bd.lasp2_attn_fwd(p, Q, K, V, None, O)
+    needs_ws = dtype == "bf16" and d == 128 and not decay
+    ws = torch.full((bd.lasp2_workspace_size(p) // 4,), float("nan"), dtype=torch.float32, device="cuda") if needs_ws else None
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, None, dQ, dK, dV, ws)
+    torch.cuda.synchronize()
+    x64 = {k: v.astype(np.float64) for k, v in x.items()}
+    if decay:
+        lam_g = np.tile(lam.astype(np.float64), B)
+        refs = (oracle.fwd_def_decay(x64["Q"], x64["K"], x64["V"], lam_g, cu),
+                *oracle.bwd_def_decay(x64["Q"], x64["K"], x64["V"], x64["dO"], lam_g, cu))
+    else:
+        refs = (oracle.fwd_def(x64["Q"], x64["K"], x64["V"], cu),
+                *oracle.bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu))
+    errs = {}
+    for name, got, ref in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), refs):
+        errs[name] = assert_close_blocks(name, to_host(got), ref, TOL[dtype])
+    print({k: f"{a:.2e}/{b:.2e}" for k, (a, b) in errs.items()}, flush=True)

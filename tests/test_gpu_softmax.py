@@ -1,11 +1,13 @@
 """GPU parity of lasp2_softmax_fwd / lasp2_softmax_bwd (softmax attention over gathered keys and values) against the
-CPU oracle, element by element on seeded inputs: fp32 and bf16, with and without the causal
-mask, query counts that are not multiples of any tile, packed documents."""
+CPU oracle on seeded inputs (every element enters; the bar is the relative L2 error of the whole
+tensor, and for sequences of at least 256 tokens also its maximum over 256-row blocks): fp32 and
+bf16, with and without the causal mask, query counts that are not multiples of any tile, packed
+documents."""
 import numpy as np
 import pytest
 
 from paper_2502_07563_amd import synth
-from tests.util import TOL, host_inputs, rel_l2, to_device, to_host
+from tests.util import TOL, host_inputs, max_block_rel_l2, rel_l2, to_device, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -47,6 +49,10 @@ def _run(oracle, B, H, N, d, dtype, seed, causal, cu=None, scale_inputs=1.0):
     assert el <= (1e-4 if dtype == "f32" else 2e-2), (eo, el)
     for k, v in eg.items():
         assert v <= TOL[dtype], (k, eg)
+    if N >= 256:
+        for n, t, r in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), (O_ref,) + tuple(refs)):
+            worst, g, row = max_block_rel_l2(to_host(t), r)
+            assert worst <= TOL[dtype], (n, g, row, worst)
 
 
 @pytest.mark.parametrize("causal", [False, True])
