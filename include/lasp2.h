@@ -198,6 +198,28 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lasp2_attn_bwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as lasp2_attn_bwd
+ * without the workspace pair; dM_t and their suffix combine go through a fixed
+ * array of LASP2_NOALLOC_SCRATCH_BYTES of device memory that is part of the
+ * loaded library (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing; its first use on a device looks the array's
+ * address up once.  LASP2_ERR_WORKSPACE if lasp2_workspace_size() exceeds
+ * LASP2_NOALLOC_SCRATCH_BYTES (at d = 128 that is B*H*T_s > 1024 slot states;
+ * the limit does not apply where lasp2_attn_bwd needs no workspace either).
+ * All calls on one GPU share the array: two calls that overlap in time on the
+ * same GPU (different streams or host threads) race and must be serialised by
+ * the caller; calls on the same stream are ordered and safe.  Nothing in the
+ * array needs clearing between calls (every state is written before it is
+ * read), and its contents after a call are unspecified.
+ */
+#define LASP2_NOALLOC_SCRATCH_BYTES (64u << 20)
+int lasp2_attn_bwd_noalloc(const lasp2_desc_t* desc, const void* Q, const void* K,
+                           const void* V, const void* dO, const float* P,
+                           void* dQ, void* dK, void* dV, void* stream);
+
+/*
  * ---- Without masking (LASP-2 paper, Sec. "LASP-2 without Masking", Algorithm
  * "LASP-2 w/o Masking" and appendix Algorithm "LASP-2 w/o Masking (Backward
  * Pass)") ----

@@ -56,6 +56,7 @@ def lib():
         L.lasp2_state_prefix.argtypes = [dp, vp, vp, ctypes.c_int, vp]
         L.lasp2_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.lasp2_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.lasp2_attn_bwd_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.lasp2_state_total.argtypes = [dp, vp, vp, vp]
         L.lasp2_nomask_fwd.argtypes = [dp, vp, vp, vp, vp]
         L.lasp2_nomask_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -69,7 +70,8 @@ def lib():
         L.lasp2_status_string.argtypes = [ctypes.c_int]
         L.lasp2_status_string.restype = ctypes.c_char_p
         for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
-                     "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_state_total",
+                     "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_attn_bwd_noalloc",
+                     "lasp2_state_total",
                      "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd",
                      "lasp2_softmax_workspace_size", "lasp2_softmax_bwd", "lasp2_softmax_fwd_share",
                      "lasp2_softmax_share_workspace_size", "lasp2_softmax_bwd_share"):
@@ -201,6 +203,17 @@ def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=Non
     _check(lib().lasp2_attn_bwd(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(P), _ptr(dQ),
                                 _ptr(dK), _ptr(dV), _ptr(workspace), ctypes.c_size_t(nbytes),
                                 _stream(stream)), "lasp2_attn_bwd")
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20     # LASP2_NOALLOC_SCRATCH_BYTES
+
+
+def lasp2_attn_bwd_noalloc(p: Problem, Q, K, V, dO, P, dQ, dK, dV, stream=None):
+    for n, t in (('Q', Q), ('K', K), ('V', V), ('dO', dO), ('dQ', dQ), ('dK', dK), ('dV', dV)):
+        _rows(p, t, p.N, n)
+    _states(p, P, 'P')
+    _check(lib().lasp2_attn_bwd_noalloc(p.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(P), _ptr(dQ),
+                                        _ptr(dK), _ptr(dV), _stream(stream)), "lasp2_attn_bwd_noalloc")
 
 
 def lasp2_state_total(p: Problem, M, S, stream=None):

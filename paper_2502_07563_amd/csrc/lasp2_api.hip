@@ -105,6 +105,93 @@ hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, fl
     return launch_states_generic(g, dtype, K, V, M, anchor_start, st);
 }
 
+// What lasp2_attn_bwd and lasp2_attn_bwd_noalloc have in common: the checks that need no
+// workspace, and the launches.
+struct BwdPlan {
+    Geom g;
+    bool empty;
+    bool fast;          // matrix-core kernels
+    bool inclusive;     // suffix states in the inclusive form
+    bool lone;          // every document a single slot
+    bool need_states;   // dM_t go through a state array of `need` bytes
+    size_t need;
+};
+
+// `workspace`: address of the caller's workspace pointer, or NULL for an entry point that has none.
+int plan_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V, const void* dO,
+                  const float* P, void* dQ, void* dK, void* dV, void* const* workspace, BwdPlan* pl)
+{
+    pl->empty = false;
+    int rc = make_geom(desc, &pl->g, &pl->empty);
+    if (rc != LASP2_OK || pl->empty) return rc;
+    const Geom& g = pl->g;
+    pl->fast = mfma_path_supported(g, desc->dtype);
+    // Which suffix states the kernels want: the plain kernels and the MFMA kernels with decay walk
+    // each slot backwards from the EXCLUSIVE suffix; the MFMA kernels without decay walk forwards
+    // from the INCLUSIVE suffix and subtract (see attn_mfma_kernel), which lets the three
+    // problems of a slot share their reads.
+    pl->inclusive = pl->fast && !g.decay;
+    // Every document a single slot (serial-carry schedule): all exclusive prefixes and suffixes are
+    // zero.  P is then not read (and may be NULL), kernels that start from the exclusive suffix need
+    // neither states nor workspace, and the inclusive suffix of a lone slot is its own state, so
+    // the combine is skipped.
+    pl->lone = g.lone_slots != 0;
+    pl->need_states = !pl->lone || pl->inclusive;
+    pl->need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    const bool ws = workspace && pl->need_states;
+    if ((!pl->lone && !P) || (ws && !*workspace)) return LASP2_ERR_NULL;   // NULL before alignment, as everywhere
+    rc = check_ptrs({Q, K, V, dO, dQ, dK, dV});
+    if (rc != LASP2_OK) return rc;
+    if ((!pl->lone && !aligned16(P)) || (ws && !aligned16(*workspace))) return LASP2_ERR_ALIGN;
+    return LASP2_OK;
+}
+
+int run_attn_bwd(const BwdPlan& pl, int dtype, const void* Q, const void* K, const void* V, const void* dO,
+                 const float* P, void* dQ, void* dK, void* dV, float* dR, hipStream_t st)
+{
+    const Geom& g = pl.g;
+    if (pl.lone) P = nullptr;
+    hipError_t e = hipSuccess;
+    if (pl.need_states) {
+        // dM_t = Q_t^T dO_t per slot, then its suffix combine in place
+        e = run_states(g, dtype, Q, dO, dR, 1, st);
+        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    }
+    if (!pl.lone) {
+        e = launch_state_prefix(g, dR, dR, 1, pl.inclusive ? 1 : 0, st);
+        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    }
+    if (pl.fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
+    // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
+    // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
+    e = launch_attn_generic(g, dtype, dO, V, K, P, dQ, 1, 0, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    // dV: anti-causal problem with (K, Q, dO); state dM_{t+1:T} = sum Q^T dO.
+    e = launch_attn_generic(g, dtype, K, Q, dO, dR, dV, 0, 1, st);
+    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
+    e = launch_attn_generic(g, dtype, V, dO, Q, dR, dK, 1, 1, st);
+    return from_hip(e);
+}
+
+// Scratch of lasp2_attn_bwd_noalloc: device memory that belongs to the loaded library itself, one
+// copy per GPU, held until the process ends.  In host code `scratch` is only a handle for the
+// symbol, not a device address: the address is asked for once per device, with that device
+// current, and kept; kernels and launchers only ever see that address.
+static __device__ __align__(256) unsigned char scratch[LASP2_NOALLOC_SCRATCH_BYTES];
+
+void* scratch_on_current_device()
+{
+    static std::atomic<void*> addr[kMaxDevices] = {};
+    const int dev = current_device_index();
+    if (dev < 0) return nullptr;
+    void* p = addr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    addr[dev].store(p, std::memory_order_release);   // the same value from whichever thread asks first
+    return p;
+}
+
 }  // namespace
 }  // namespace lasp2
 
@@ -181,54 +268,31 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
                    const void* dO, const float* P, void* dQ, void* dK, void* dV,
                    void* workspace, size_t workspace_bytes, void* stream)
 {
-    Geom g;
-    bool empty = false;
-    int rc = make_geom(desc, &g, &empty);
+    BwdPlan pl;
+    int rc = plan_attn_bwd(desc, Q, K, V, dO, P, dQ, dK, dV, &workspace, &pl);
     if (rc != LASP2_OK) return rc;
-    if (empty) return LASP2_OK;
-    const bool fast = mfma_path_supported(g, desc->dtype);
-    // Which suffix states the kernels want: the plain kernels and the MFMA kernels with decay walk
-    // each slot backwards from the EXCLUSIVE suffix; the MFMA kernels without decay walk forwards
-    // from the INCLUSIVE suffix and subtract (see attn_mfma_kernel), which lets the three
-    // problems of a slot share their reads.
-    const bool inclusive = fast && !g.decay;
-    // Every document a single slot (serial-carry schedule): all exclusive prefixes and suffixes are
-    // zero.  P is then not read (and may be NULL), kernels that start from the exclusive suffix need
-    // neither states nor workspace, and the inclusive suffix of a lone slot is its own state, so
-    // the combine is skipped.
-    const bool lone = g.lone_slots != 0;
-    const bool need_states = !lone || inclusive;
-    if ((!lone && !P) || (need_states && !workspace)) return LASP2_ERR_NULL;   // NULL before alignment, as everywhere
-    rc = check_ptrs({Q, K, V, dO, dQ, dK, dV});
-    if (rc != LASP2_OK) return rc;
-    if ((!lone && !aligned16(P)) || (need_states && !aligned16(workspace))) return LASP2_ERR_ALIGN;
-    size_t need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
-    if (need_states && workspace_bytes < need) return LASP2_ERR_WORKSPACE;
-    if (lone) P = nullptr;
+    if (pl.empty) return LASP2_OK;
+    if (pl.need_states && workspace_bytes < pl.need) return LASP2_ERR_WORKSPACE;
+    return run_attn_bwd(pl, desc->dtype, Q, K, V, dO, P, dQ, dK, dV,
+                        pl.need_states ? static_cast<float*>(workspace) : nullptr, (hipStream_t)stream);
+}
 
-    hipStream_t st = (hipStream_t)stream;
-    float* dR = need_states ? static_cast<float*>(workspace) : nullptr;
-    hipError_t e = hipSuccess;
-    if (need_states) {
-        // dM_t = Q_t^T dO_t per slot, then its suffix combine in place
-        e = run_states(g, desc->dtype, Q, dO, dR, 1, st);
-        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
+int lasp2_attn_bwd_noalloc(const lasp2_desc_t* desc, const void* Q, const void* K, const void* V,
+                           const void* dO, const float* P, void* dQ, void* dK, void* dV, void* stream)
+{
+    BwdPlan pl;
+    int rc = plan_attn_bwd(desc, Q, K, V, dO, P, dQ, dK, dV, nullptr, &pl);
+    if (rc != LASP2_OK) return rc;
+    if (pl.empty) return LASP2_OK;
+    float* dR = nullptr;
+    if (pl.need_states) {
+        if (pl.need > (size_t)LASP2_NOALLOC_SCRATCH_BYTES) return LASP2_ERR_WORKSPACE;
+        dR = static_cast<float*>(scratch_on_current_device());
+        if (!dR) return LASP2_ERR_LAUNCH;
     }
-    if (!lone) {
-        e = launch_state_prefix(g, dR, dR, 1, inclusive ? 1 : 0, st);
-        if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    }
-    if (fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
-    // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
-    // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
-    e = launch_attn_generic(g, desc->dtype, dO, V, K, P, dQ, 1, 0, st);
-    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    // dV: anti-causal problem with (K, Q, dO); state dM_{t+1:T} = sum Q^T dO.
-    e = launch_attn_generic(g, desc->dtype, K, Q, dO, dR, dV, 0, 1, st);
-    if (e != hipSuccess) return LASP2_ERR_LAUNCH;
-    // dK: anti-causal problem with (V, dO, Q); state dO^T Q = dM^T.
-    e = launch_attn_generic(g, desc->dtype, V, dO, Q, dR, dK, 1, 1, st);
-    return from_hip(e);
+    // Nothing in the array has to start at zero: the states kernel writes every slot's state
+    // before the combine and the attention kernels read any of it.
+    return run_attn_bwd(pl, desc->dtype, Q, K, V, dO, P, dQ, dK, dV, dR, (hipStream_t)stream);
 }
 
 int lasp2_state_total(const lasp2_desc_t* desc, const float* M, float* S, void* stream)

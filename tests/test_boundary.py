@@ -33,6 +33,7 @@ def test_header_symbols_are_exported():
     names = set(re.findall(r"\b(lasp2_[a-z0-9_]+)\s*\(", text))
     assert {"lasp2_chunk_states", "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd",
             "lasp2_num_slots", "lasp2_workspace_size", "lasp2_status_string", "lasp2_state_total",
+            "lasp2_attn_bwd_noalloc",
             "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd", "lasp2_softmax_bwd",
             "lasp2_softmax_workspace_size", "lasp2_softmax_fwd_share", "lasp2_softmax_bwd_share",
             "lasp2_softmax_share_workspace_size"} <= names
@@ -174,6 +175,29 @@ def test_null_prefix_is_accepted_only_when_every_sequence_is_one_slot():
     pk = lambda L: ctypes.byref(_desc(C=128, L=L, n_seqs=4, cu_seqlens_host=cu.ctypes.data, cu_seqlens_dev=0x2000))
     assert lib.lasp2_attn_fwd(pk(768), FAKE, FAKE, FAKE, None, ODD, None) == -6      # longest document: 723 tokens
     assert lib.lasp2_attn_fwd(pk(640), FAKE, FAKE, FAKE, None, ODD, None) == -1      # ... now two slots
+
+
+def test_noalloc_backward_argument_errors():
+    """lasp2_attn_bwd_noalloc: the same checks as lasp2_attn_bwd, and a problem whose state array
+    does not fit the library's fixed device array is refused, all before any device work."""
+    lib = B.lib()
+    r = ctypes.byref(_desc())
+    args = [FAKE] * 8
+    for i in range(8):
+        a = list(args); a[i] = None
+        assert lib.lasp2_attn_bwd_noalloc(r, *a, None) == -1
+    a = list(args); a[7] = ODD
+    assert lib.lasp2_attn_bwd_noalloc(r, *a, None) == -6
+    assert lib.lasp2_attn_bwd_noalloc(None, *args, None) == -1
+    big = _desc(B=1, H=1, N=1025 * 256, d=128, C=256, L=256, dtype=B.LASP2_BF16)      # 1025 states of 64 KiB
+    need = ctypes.c_size_t(0)
+    assert lib.lasp2_workspace_size(ctypes.byref(big), ctypes.byref(need)) == 0 and need.value == 1025 * 65536
+    assert need.value > B.NOALLOC_SCRATCH_BYTES
+    assert lib.lasp2_attn_bwd_noalloc(ctypes.byref(big), *args, None) == -5
+    text = open(os.path.join(ROOT, "include", "lasp2.h")).read()
+    assert re.search(r"#define\s+LASP2_NOALLOC_SCRATCH_BYTES\s+\(64u << 20\)", text) and B.NOALLOC_SCRATCH_BYTES == 64 << 20
+    # empty problems need nothing
+    assert lib.lasp2_attn_bwd_noalloc(ctypes.byref(_desc(N=0)), *([None] * 8), None) == 0
 
 
 def test_decay_errors():
