@@ -206,7 +206,7 @@ def main():
     Q, K, V, dO = mk(), mk(), mk(), mk()
     O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
     P = bd.alloc_states(p)
-    ws = bd.alloc_states(p)
+    ws = bd.alloc_workspace(p)
     T_s = P.shape[2]
     # One slot per sequence (e.g. --slot-len N): the serial-carry schedule.  Every prefix is zero, so
     # the step makes no chunk_states / state_prefix call and hands P = NULL to both attention calls.

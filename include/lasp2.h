@@ -133,7 +133,9 @@ typedef struct lasp2_desc {
 int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s);
 
 /* Bytes of device scratch lasp2_attn_bwd and lasp2_nomask_bwd need: one fp32 state array
- * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine. */
+ * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine, followed by one 32-bit
+ * counter per (b,h,slot) with which the backward's workgroups that read the same slot keep in
+ * step (a matter of speed only: no result depends on a counter). */
 int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
 
 /*
@@ -206,15 +208,16 @@ int lasp2_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K,
  * loaded library (one copy per GPU, held until the process ends).  The call
  * allocates and frees nothing; its first use on a device looks the array's
  * address up once.  LASP2_ERR_WORKSPACE if lasp2_workspace_size() exceeds
- * LASP2_NOALLOC_SCRATCH_BYTES (at d = 128 that is B*H*T_s > 1024 slot states;
- * the limit does not apply where lasp2_attn_bwd needs no workspace either).
+ * LASP2_NOALLOC_SCRATCH_BYTES (at d = 128 that is B*H*T_s > 1024 slot states,
+ * 64 MiB of states and their counters; the limit does not apply where
+ * lasp2_attn_bwd needs no workspace either).
  * All calls on one GPU share the array: two calls that overlap in time on the
  * same GPU (different streams or host threads) race and must be serialised by
  * the caller; calls on the same stream are ordered and safe.  Nothing in the
  * array needs clearing between calls (every state is written before it is
  * read), and its contents after a call are unspecified.
  */
-#define LASP2_NOALLOC_SCRATCH_BYTES (64u << 20)
+#define LASP2_NOALLOC_SCRATCH_BYTES ((64u << 20) + (64u << 10))
 int lasp2_attn_bwd_noalloc(const lasp2_desc_t* desc, const void* Q, const void* K,
                            const void* V, const void* dO, const float* P,
                            void* dQ, void* dK, void* dV, void* stream);

@@ -205,7 +205,7 @@ def lasp2_attn_bwd(p: Problem, Q, K, V, dO, P, dQ, dK, dV, workspace, stream=Non
                                 _stream(stream)), "lasp2_attn_bwd")
 
 
-NOALLOC_SCRATCH_BYTES = 64 << 20     # LASP2_NOALLOC_SCRATCH_BYTES
+NOALLOC_SCRATCH_BYTES = (64 << 20) + (64 << 10)     # LASP2_NOALLOC_SCRATCH_BYTES
 
 
 def lasp2_attn_bwd_noalloc(p: Problem, Q, K, V, dO, P, dQ, dK, dV, stream=None):
@@ -294,6 +294,18 @@ def alloc_states(p: Problem, device="cuda"):
     return torch.empty((p.B, p.H, lasp2_num_slots(p), p.d, p.d), dtype=torch.float32, device=device)
 
 
+def alloc_workspace(p: Problem, device="cuda"):
+    """Scratch for lasp2_attn_bwd / lasp2_nomask_bwd: lasp2_workspace_size(p) bytes as a flat fp32 array
+    (the state array first, then the backward's pacing counters)."""
+    return torch.empty(lasp2_workspace_size(p) // 4, dtype=torch.float32, device=device)
+
+
+def workspace_states(p: Problem, ws):
+    """The fp32 [B,H,T_s,d,d] state array at the head of a workspace."""
+    T_s = lasp2_num_slots(p)
+    return ws[:p.B * p.H * T_s * p.d * p.d].view(p.B, p.H, T_s, p.d, p.d)
+
+
 def forward(p: Problem, Q, K, V, stream=None):
     """chunk_states -> state_prefix (in place) -> attn_fwd.  Returns (O, P)."""
     P = alloc_states(p, Q.device)
@@ -305,11 +317,11 @@ def forward(p: Problem, Q, K, V, stream=None):
 
 
 def backward(p: Problem, Q, K, V, dO, P, stream=None):
-    """attn_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, workspace)."""
-    ws = alloc_states(p, Q.device)
+    """attn_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, the workspace's state array)."""
+    ws = alloc_workspace(p, Q.device)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws, stream)
-    return dQ, dK, dV, ws
+    return dQ, dK, dV, workspace_states(p, ws)
 
 
 def nomask_forward(p: Problem, Q, K, V, stream=None):
@@ -323,8 +335,8 @@ def nomask_forward(p: Problem, Q, K, V, stream=None):
 
 
 def nomask_backward(p: Problem, Q, K, V, dO, S, stream=None):
-    """nomask_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, workspace)."""
-    ws = alloc_states(p, Q.device)
+    """nomask_bwd with a freshly allocated workspace.  Returns (dQ, dK, dV, the workspace's state array)."""
+    ws = alloc_workspace(p, Q.device)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     lasp2_nomask_bwd(p, Q, K, V, dO, S, dQ, dK, dV, ws, stream)
-    return dQ, dK, dV, ws
+    return dQ, dK, dV, workspace_states(p, ws)

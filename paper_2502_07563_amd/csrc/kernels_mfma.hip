@@ -314,7 +314,25 @@ struct AttnProblem {
     char* out;
     int transpose_state;  // read the d x d slot state transposed
     int anti;             // 0: causal (j <= i); 1: anti-causal (j >= i)
+    const unsigned* pace; // NULL, or per (group, slot): 64-token blocks another workgroup has begun
+    int lead;             // with pace: this walk may be at most `lead` blocks ahead of that count
 };
+
+// Holds wave 0 of a walk (and with it, at the next barrier, its workgroup) until the workgroup it
+// shares its reads with has begun block `need`, so that the two stay within reach of each other
+// in the L2.  Purely a matter of speed: the count is read through the scalar cache with glc (a
+// scalar load does not disturb the vector-memory counter the walk's own waits rely on), no data
+// depends on it, and the wait gives up after a bounded number of polls.
+__device__ __forceinline__ void pace_wait(const unsigned* p, int need)
+{
+    if (need <= 0) return;
+    for (int i = 0; i < 512; ++i) {
+        unsigned v;
+        asm volatile("s_load_dword %0, %1, 0x0 glc\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+        if ((int)v >= need) break;
+        __builtin_amdgcn_s_sleep(4);
+    }
+}
 
 // Snapshot of the running state for the inter-chunk product: bf16 [d_v][d_k] in LDS.
 // negate: the accumulators hold minus the state (anti-causal walk, see the kernel).
@@ -956,6 +974,8 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
                 *pk = scale_bf16x8(*pk, wr);
             }
         }
+        // (blocks past the slot's end exist only in this walk's padding: nothing to wait for there)
+        if (pr.pace && w == 0 && blk(bi) * KB < len) pace_wait(pr.pace + ((size_t)grp * g.T_s + s), bi - pr.lead);
         __syncthreads();
         seq_cur = seq_next;
         if (bi + 2 < NBP && blk(bi + 2) * KB < len) { issue(bi + 2); issued += DPS; }
@@ -1185,6 +1205,436 @@ __global__ __launch_bounds__(512) void attn_skew_mfma_kernel(Geom g, AttnProblem
     }
 }
 
+// =====================================================================================
+// The anti-causal pair of the backward in one workgroup:
+//   dV_j = sum_{i>=j} (q_i . k_j) dO_i ,   dK_j = sum_{i>=j} (dO_i . v_j) q_i
+// (i, j over the tokens of j's document).  Both stream the same rows (Q and dO) and carry the
+// same running state sum q^T dO, so one workgroup stages each 64-token block of Q and dO once
+// and updates the state once for both: waves 0-3 own 32 rows each of a 128-row chunk for dV
+// (their rows of K held as operand fragments, scores against the Q tile, dO tile mixed in) and
+// waves 4-7 the same rows for dK (rows of V, scores against the dO tile, Q tile mixed in); all
+// eight share the 16 state tiles, two each.  The state's bf16 snapshot is written once per
+// chunk, [d_v][d_k]: the dV waves read it row-wise, the dK waves through the transposing LDS
+// read, which hands them its transpose.  Waves s and s+4 share a SIMD and own row blocks s and
+// 3-s, so that the triangular work of the two adds up evenly.
+// Against two separate problems this saves half the stage loads, one of the two state updates
+// (an eighth of the matrix-core work of the pair) and one snapshot per chunk.
+//
+// Walk: forwards, like the causal problem that shares the launch (and with it the L2 copies of K,
+// V and dO).  The accumulators start from minus the inclusive suffix R at the slot's start and
+// add q^T dO block by block, so on entering chunk c they hold minus R_c, the sum over chunk c and
+// everything after it.  A row takes that state on ENTRY and subtracts what lies before it inside
+// the chunk:  dV_j = k_j R_c - sum_{i<j, i in c} (q_i . k_j) dO_i  (dK alike).  The masked
+// products therefore run over the strictly lower triangle (score tiles up to the row's own, the
+// same number as for i >= j), a row is complete as soon as the walk has passed its own 32-row
+// tile, and its fragments are then free for the next chunk's rows: row blocks 0 and 1 finish in
+// the chunk's first 64-token block and request their next rows there, row blocks 2 and 3 in the
+// second (template parameter LATE); all store in the second block, the early ones while the late
+// ones still compute.  Every chunk is walked as two blocks; one that lies wholly past the slot's
+// end is zeroed, not loaded.  Loads, counted waits (kept at run time as in skew_walk) and stores
+// as in the other walks.
+// =====================================================================================
+struct PairProblem {
+    const char* Q;
+    const char* dO;
+    const char* K;
+    const char* V;
+    const float* dR;   // [G][T_s][d][d]: inclusive suffix of Q^T dO at each slot's start
+    char* dV;
+    char* dK;
+    unsigned* pace;    // NULL, or per (group, slot): receives the number of blocks this walk has begun
+};
+
+template <bool DKROLE, bool LATE>
+__device__ __forceinline__ void pair_walk(const Geom& g, const PairProblem& pr, char* smem, int tid, int w,
+                                          int rb, int grp, int s, int tok0, int len)
+{
+    constexpr int C = 128, NW = 8, TPW = 2, BPC = C / KB, IPW = 16 / NW, DPS = 2 * IPW, NOP = 4;
+    char* sX = smem;                              // Q stages
+    char* sY = smem + NSTAGE * STAGE_BYTES;       // dO stages
+    char* sM = smem + 2 * NSTAGE * STAGE_BYTES;   // state snapshot, bf16 [d_v][d_k]
+    char* sO = sM + D * ROWB;                     // output staging, 4 KiB per wave
+    const int lane = tid & 63, h = lane >> 5, l32 = lane & 31;
+    const char* __restrict__ A = DKROLE ? pr.V : pr.K;
+    char* __restrict__ out = DKROLE ? pr.dK : pr.dV;
+    const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
+    const int t0 = w * TPW;
+    const int nch = (len + C - 1) / C;
+    const int NBP = nch * BPC;             // blocks walked (the last chunk padded to two)
+    // Stage loads of block i.  The per-lane source offsets are rebuilt at every call from a lane index
+    // the compiler cannot hoist: kept across the walk they cost registers this kernel does not have.
+    auto issue = [&](int i) __attribute__((always_inline)) {
+        int ln;
+        asm volatile("v_and_b32 %0, 63, %1" : "=v"(ln) : "v"(tid));
+        uint32_t dvo[IPW];
+#pragma unroll
+        for (int u = 0; u < IPW; ++u) dvo[u] = dma_lane_off(w * IPW + u, ln);
+        dma_block<NW>(pr.Q, pr.dO, row0, i * KB, len, sX + (i % NSTAGE) * STAGE_BYTES,
+                      sY + (i % NSTAGE) * STAGE_BYTES, w, ln, dvo);
+    };
+    issue(0);
+    if (KB < len) issue(1);
+
+    // running state tiles (rows d_k, columns d_v), holding minus the suffix
+    f32x16 Macc[TPW];
+    {
+        const float* st = pr.dR + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+            const int t = t0 + u, a = t >> 2, b = t & 3;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                Macc[u][v] = -st[(32 * a + 8 * (v >> 2) + 4 * h + (v & 3)) * D + 32 * b + l32];
+        }
+    }
+
+    // Per-lane byte offsets into a swizzled tile, one register per family as in skew_walk (the
+    // swizzle is an XOR on the 16-byte chunk index, so the members of a family differ by an XOR
+    // with a constant and a multiple of the row size):
+    //   natural row l32, d step ks:                        nat0 ^ (ks << 5)
+    //   transposed fetch of columns 32 tv + l32, rows r:   pvA ^ (tv << 6);  rows r + 8: (.. ^ 32) + 8 rows
+    //   state update, X^T operand, rows r:                 uaA;              rows r + 4: (uaA ^ 16) + 4 rows
+    //   state update, Y operand of tile u:                 uaA ^ ydel ^ (u << 6), ydel the same in all lanes
+    //   snapshot read transposed (dK), columns 32 t + l32: uaA ^ xdel ^ (t << 6), rows r + 4 as above
+    const int li = lane & 15, g2 = (lane >> 4) & 1, cl = 16 * g2 + 4 * (li & 3), rl = li >> 2;
+    const uint32_t nat0 = (uint32_t)tile_off(l32, h);
+    const uint32_t pvA = (uint32_t)tr_off(4 * h + rl, cl);
+    const uint32_t uaA = (uint32_t)tr_off(8 * h + rl, 32 * (t0 >> 2) + cl);
+    const uint32_t ydel = (uint32_t)(((t0 >> 2) ^ (t0 & 3)) << 6);
+    const uint32_t xdel = (uint32_t)((t0 >> 2) << 6);
+
+    // this wave's 32 rows of A as B-operand fragments, fetched asynchronously (see attn_mfma_kernel);
+    // rows past the slot's end fetch its last row
+    u32x4 qv[8];
+    auto issue_q = [&](int c) __attribute__((always_inline)) {
+        int lrow;   // lane % 32 in a form the compiler cannot hoist out of the chunk loop (and spill)
+        asm volatile("v_and_b32 %0, 31, %1" : "=v"(lrow) : "v"(tid));
+        const int r = min(c * C + 32 * rb + lrow, len - 1);
+        const char* p = A + row0 + (size_t)r * ROWB + 16 * h;
+        gload16_async<0>(qv[0], p);
+        gload16_async<32>(qv[1], p);
+        gload16_async<64>(qv[2], p);
+        gload16_async<96>(qv[3], p);
+        gload16_async<128>(qv[4], p);
+        gload16_async<160>(qv[5], p);
+        gload16_async<192>(qv[6], p);
+        gload16_async<224>(qv[7], p);
+    };
+    auto take_q = [&](uint32_t zero) __attribute__((always_inline)) {
+        const u32x4 z = {zero, zero, zero, zero};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qv[ks] = qv[ks] | z;
+    };
+    issue_q(0);
+    take_q(wait_vmcnt_token<0>());   // also completes blocks 0 and 1 and the state
+    const bf16x8 (&qf)[8] = reinterpret_cast<const bf16x8 (&)[8]>(qv);
+
+    f32x16 Oacc[4];
+    auto zero_out = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int tv = 0; tv < 4; ++tv)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Oacc[tv][v] = 0.f;
+    };
+
+    // vector-memory instructions certainly issued since the full wait above, and the marks of the
+    // batches to wait for (see wait_vmcnt_le)
+    int issued = 0, seq_cur = 0, seq_next = 0, seq_q = 0;
+
+    char* tX = sX;
+    char* tY = sY;
+    // start of block bi: its loads have landed, the block is complete in LDS, every wave is past
+    // block bi - 1, and the loads of block bi + 2 are on their way
+    auto begin = [&](int bi) __attribute__((always_inline)) {
+        tX = sX + (bi % NSTAGE) * STAGE_BYTES;
+        tY = sY + (bi % NSTAGE) * STAGE_BYTES;
+        wait_vmcnt_le(issued - seq_cur);
+        if (bi * KB + KB > len) zero_tail_rows<NW>(bi * KB, len, tX, tY, w, lane);
+        __syncthreads();
+        if (pr.pace && w == 0) {
+            if (lane == 0) __hip_atomic_store(pr.pace + ((size_t)grp * g.T_s + s), (unsigned)(bi + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            issued += 1;
+        }
+        seq_cur = seq_next;
+        if (bi + 2 < NBP && (bi + 2) * KB < len) { issue(bi + 2); issued += DPS; }
+        seq_next = issued;
+    };
+
+    auto request_rows = [&](int c) __attribute__((always_inline)) {
+        issue_q(c);
+        issued += 8;
+        seq_q = issued;
+    };
+
+    // The masked products of this wave's rows with the two 32-row tiles of block JB of the chunk, in
+    // one of two forms.  EXIT: the rows take the state at the chunk's exit and GAIN what follows them
+    // inside the chunk: their own tile from the diagonal on and the tiles after it.  Otherwise: the
+    // rows take the state at the chunk's entry and LOSE what precedes them inside the chunk: the
+    // tiles before their own, and their own strictly below the diagonal, all with a minus sign.
+    auto tiles = [&](auto jb_c, auto exit_c) __attribute__((always_inline)) {
+        constexpr int JB = decltype(jb_c)::value;
+        constexpr bool EXIT = decltype(exit_c)::value;
+        // rows scored against this wave's rows (S), rows mixed by the scores (C)
+        const uint32_t aS = lds_addr_of(DKROLE ? tY : tX) + nat0, aC = lds_addr_of(DKROLE ? tX : tY) + pvA;
+        bf16x8 bufA[NOP], bufB[NOP];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int kt = 2 * JB + half;      // 32-row tile of the streamed rows inside the chunk
+            if (EXIT ? kt < rb : kt > rb) continue;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufA[ks] = lds_read16_u((aS ^ (ks << 5)) + half * (32 * ROWB));
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bufB[ks] = lds_read16_u((aS ^ ((ks + 4) << 5)) + half * (32 * ROWB));
+            SCHED_FENCE();
+            f32x16 sc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufA[ks], qf[ks], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufA[tv] = lds_read_tr8_u((aC ^ (tv << 6)) + half * (32 * ROWB),
+                                          (aC ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 8 * ROWB);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sc = mfma(bufB[ks], qf[ks + 4], sc);
+            SCHED_FENCE();
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv)
+                bufB[tv] = lds_read_tr8_u((aC ^ (tv << 6)) + half * (32 * ROWB) + 16 * ROWB,
+                                          (aC ^ ((tv << 6) | 32)) + half * (32 * ROWB) + 24 * ROWB);
+            SCHED_FENCE();
+            if (kt == rb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+                    const bool keep = EXIT ? key >= l32 : key < l32;
+                    sc[v] = keep ? sc[v] : 0.f;
+                }
+            }
+            constexpr float sg = EXIT ? 1.f : -1.f;
+            {
+                u32x4 pk = {pack2(sg * sc[0], sg * sc[1]), pack2(sg * sc[2], sg * sc[3]), pack2(sg * sc[4], sg * sc[5]),
+                            pack2(sg * sc[6], sg * sc[7])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufA[tv], sb, Oacc[tv]);
+            }
+            {
+                u32x4 pk = {pack2(sg * sc[8], sg * sc[9]), pack2(sg * sc[10], sg * sc[11]), pack2(sg * sc[12], sg * sc[13]),
+                            pack2(sg * sc[14], sg * sc[15])};
+                bf16x8 sb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bufB[tv], sb, Oacc[tv]);
+            }
+            SCHED_FENCE();
+        }
+    };
+
+    // running state += Q_blk^T dO_blk on this wave's two tiles, 16 tokens per step
+    auto update = [&]() __attribute__((always_inline)) {
+        const uint32_t aXA = lds_addr_of(tX) + uaA, aYA = lds_addr_of(tY) + (uaA ^ ydel);
+        bf16x8 bufA[NOP], bufB[NOP];
+        // operands of 16-token step ks: buf[0] = X^T rows of the wave's tile row, buf[1 + u] = Y
+        // columns of tile u
+        auto rd_upd = [&](bf16x8 (&buf)[NOP], int ks) __attribute__((always_inline)) {
+            buf[0] = lds_read_tr8_u(aXA + ks * (16 * ROWB), (aXA ^ 16) + ks * (16 * ROWB) + 4 * ROWB);
+#pragma unroll
+            for (int u = 0; u < TPW; ++u)
+                buf[1 + u] = lds_read_tr8_u((aYA ^ (u << 6)) + ks * (16 * ROWB),
+                                            (aYA ^ ((u << 6) | 16)) + ks * (16 * ROWB) + 4 * ROWB);
+        };
+        rd_upd(bufA, 0);
+        SCHED_FENCE();
+        rd_upd(bufB, 1);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufA);
+        SCHED_FENCE();
+        rd_upd(bufA, 2);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufB);
+        SCHED_FENCE();
+        rd_upd(bufB, 3);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufA);
+        SCHED_FENCE();
+        mm_update<TPW, NOP>(Macc, bufB);
+        SCHED_FENCE();
+    };
+
+    // inter-chunk term from the snapshot of the state at the chunk's entry
+    auto inter = [&]() __attribute__((always_inline)) {
+        bf16x8 bA[NOP], bB[NOP];
+        if (!DKROLE) {
+            // out^T (d_v x rows) += S^T (d_v x d_k) K_w^T: snapshot rows as they lie
+            const uint32_t aM = lds_addr_of(sM) + nat0;
+#pragma unroll
+            for (int tv = 0; tv < 4; ++tv) bA[tv] = lds_read16_u(aM + tv * (32 * ROWB));
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 8; ks += 2) {
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) bB[tv] = lds_read16_u((aM ^ ((ks + 1) << 5)) + tv * (32 * ROWB));
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bA[tv], qf[ks], Oacc[tv]);
+                SCHED_FENCE();
+                if (ks + 2 < 8) {
+#pragma unroll
+                    for (int tv = 0; tv < 4; ++tv) bA[tv] = lds_read16_u((aM ^ ((ks + 2) << 5)) + tv * (32 * ROWB));
+                }
+                SCHED_FENCE();
+#pragma unroll
+                for (int tv = 0; tv < 4; ++tv) Oacc[tv] = mfma(bB[tv], qf[ks + 1], Oacc[tv]);
+                SCHED_FENCE();
+            }
+        } else {
+            // out^T (d_k x rows) += S (d_k x d_v) V_w^T: the snapshot read transposed
+            const uint32_t aT = lds_addr_of(sM) + (uaA ^ xdel);
+            auto rd = [&](bf16x8 (&buf)[NOP], int ks) __attribute__((always_inline)) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    buf[t] = lds_read_tr8_u((aT ^ (t << 6)) + ks * (16 * ROWB),
+                                            (aT ^ ((t << 6) | 16)) + ks * (16 * ROWB) + 4 * ROWB);
+            };
+            rd(bA, 0);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < 8; ks += 2) {
+                rd(bB, ks + 1);
+                SCHED_FENCE();
+#pragma unroll
+                for (int t = 0; t < 4; ++t) Oacc[t] = mfma(bA[t], qf[ks], Oacc[t]);
+                SCHED_FENCE();
+                if (ks + 2 < 8) rd(bA, ks + 2);
+                SCHED_FENCE();
+#pragma unroll
+                for (int t = 0; t < 4; ++t) Oacc[t] = mfma(bB[t], qf[ks + 1], Oacc[t]);
+                SCHED_FENCE();
+            }
+        }
+    };
+
+    // stores this wave's rows of chunk c (none when there is no such chunk) and clears the accumulators
+    auto store_rows = [&](int c) __attribute__((always_inline)) {
+        const int rbase = c * C + 32 * rb;
+        const int nrows = c < 0 ? 0 : len - rbase;
+        store_out_rows(Oacc, sO + w * 4096, out + row0 + (ptrdiff_t)rbase * ROWB, nrows, tid);
+        if (nrows >= 32) issued += 8;   // all eight stores certainly execute
+        SCHED_FENCE();
+        zero_out();
+    };
+
+    using std::integral_constant;
+    constexpr integral_constant<int, 0> B0{};
+    constexpr integral_constant<int, 1> B1{};
+    constexpr integral_constant<bool, false> ENTRY{};
+    constexpr integral_constant<bool, true> EXIT{};
+
+    // Rows 0..63 of a chunk (row blocks 0, 1; !LATE) use the entry form: they are complete after
+    // the chunk's first block, are stored in its second, and their fragments are free for the next
+    // chunk's rows a whole block before those are needed.  Rows 64..127 (LATE) use the exit form:
+    // their tiles lie in the chunk's second block, the state at its exit is the snapshot at the
+    // top of the NEXT chunk, so they are completed and stored in that chunk's first block, where
+    // they also request their next rows.  Every snapshot thus serves both kinds of rows, and each
+    // wave has a tile-free block per chunk for its stores and row fetches.
+    // The slot's LAST chunk uses the exit form for all rows, against the state at the slot's end:
+    // the entry form subtracts two sums of rounded terms, which is harmless while many later tokens
+    // contribute to a row, but where a document ends inside or right after the chunk a row may
+    // keep only a few terms, and those would then carry the rounding of all the cancelled ones.
+    zero_out();
+    const int n_loop = LATE ? nch : nch - 1;
+    for (int c = 0; c < n_loop; ++c) {
+        const int bi = c * BPC;
+        // The state as the walk enters the chunk.  The previous chunk read its snapshot in its
+        // first block; its second block's barrier lies in between.
+        write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
+
+        // ---- block 0
+        begin(bi);
+        if (!LATE) {
+            take_q(wait_vmcnt_token_le(issued - seq_q));
+            inter();
+            tiles(B0, ENTRY);
+            request_rows(c + 1);   // the fragments are free for the next chunk's rows
+        } else {
+            // finish the rows of the previous chunk (at c = 0: the rows fetched before the walk, for
+            // nothing; they are not stored), then ask for this chunk's
+            inter();
+            request_rows(c);
+            store_rows(c - 1);
+        }
+        update();
+
+        // ---- block 1
+        begin(bi + 1);
+        if (!LATE) {
+            store_rows(c);
+        } else {
+            take_q(wait_vmcnt_token_le(issued - seq_q));
+            tiles(B1, EXIT);
+        }
+        update();
+    }
+    if (!LATE) {
+        // the last chunk, rows 0..63 in the exit form
+        const int bi = (nch - 1) * BPC;
+        write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
+        begin(bi);
+        take_q(wait_vmcnt_token_le(issued - seq_q));
+        tiles(B0, EXIT);
+        update();
+        begin(bi + 1);
+        tiles(B1, EXIT);
+        update();
+    }
+    // the state beyond the slot's last chunk, for the rows that await it
+    write_snapshot<TPW>(sM, Macc, t0, l32, h, true);
+    __syncthreads();
+    inter();
+    store_rows(nch - 1);
+    // nothing left to keep in step with: release a partner that counts blocks this walk does not have
+    // (the other walk pads its chunks to 256 rows)
+    if (pr.pace && w == 0 && lane == 0)
+        __hip_atomic_store(pr.pace + ((size_t)grp * g.T_s + s), 0x7fffffffu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void zero_u32_kernel(unsigned* p, unsigned n)
+{
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// The backward's attention launch for slots longer than 128 tokens, without decay: per (group,
+// slot) one workgroup for the anti-causal pair (pair_walk) and one for dQ (the causal skew_walk),
+// dealt to the same XCD like the problems of attn_skew_mfma_kernel; the pair's workgroup, which
+// has more to do, comes first in the grid.
+__global__ __launch_bounds__(512) void attn_bwd_pair_mfma_kernel(Geom g, AttnProblem pq, PairProblem pp)
+{
+    extern __shared__ __attribute__((aligned(256))) char smem[];
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned unit = (blockIdx.x / 16u) * 8u + (blockIdx.x & 7u);
+    const int prob = (int)(blockIdx.x >> 3) & 1;
+    if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
+    const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
+    int tok0, len;
+    slot_range(g, s, tok0, len);
+    if (len <= 0) return;
+    if (prob == 0) {
+        // waves s and s+4 share a SIMD: row block s for dV, 3-s for dK
+        if (w < 2) pair_walk<false, false>(g, pp, smem, tid, w, w, grp, s, tok0, len);
+        else if (w < 4) pair_walk<false, true>(g, pp, smem, tid, w, w, grp, s, tok0, len);
+        else if (w < 6) pair_walk<true, true>(g, pp, smem, tid, w, 7 - w, grp, s, tok0, len);
+        else pair_walk<true, false>(g, pp, smem, tid, w, 7 - w, grp, s, tok0, len);
+    } else {
+        const int rb = w < 4 ? w : 11 - w;
+        if (rb < 4) skew_walk<false, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len);
+        else skew_walk<true, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len);
+    }
+}
+
 template <int C>
 hipError_t launch_attn_C(const Geom& g, const AttnProblem& p0, const AttnProblem& p1,
                          const AttnProblem& p2, int nprob, hipStream_t st)
@@ -1224,7 +1674,7 @@ AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const fl
 {
     return AttnProblem{static_cast<const char*>(A), static_cast<const char*>(Bk),
                        static_cast<const char*>(Cv), state, static_cast<char*>(out), transpose_state,
-                       anti};
+                       anti, nullptr, 0};
 }
 
 // =====================================================================================
@@ -1712,8 +2162,8 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
 }
 
 hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
-                                const void* dO, const float* P, const float* dR, void* dQ, void* dK,
-                                void* dV, hipStream_t st)
+                                const void* dO, const float* P, const float* dR, unsigned* pace, void* dQ,
+                                void* dK, void* dV, hipStream_t st)
 {
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state V^T K is the
     //     cached prefix read transposed.
@@ -1723,7 +2173,27 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
     const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
     if (g.decay) return launch_attn_decay(g, pq, pv, pk, 3, st);
-    if (wide_chunks(g)) return launch_attn_skew<false>(g, pq, pv, pk, 3, st);
+    if (wide_chunks(g)) {
+        constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 8 * 4096;
+        hipError_t e = allow_dynamic_lds<attn_bwd_pair_mfma_kernel>(smem);
+        if (e != hipSuccess) return e;
+        // The two workgroups of a slot share their reads of K, V and dO through the L2 only while
+        // they stay close: the pair's workgroup counts the blocks it has begun in pace[unit], and the
+        // faster dQ walk does not run ahead of that count.
+        const unsigned units = (unsigned)g.T_s * (unsigned)g.G;
+        AttnProblem pq2 = pq;
+        if (pace) {
+            hipLaunchKernelGGL(zero_u32_kernel, dim3((units + 255u) / 256u), dim3(256), 0, st, pace, units);
+            pq2.pace = pace;
+            pq2.lead = 0;
+        }
+        const PairProblem pp = {static_cast<const char*>(Q), static_cast<const char*>(dO),
+                                static_cast<const char*>(K), static_cast<const char*>(V), dR,
+                                static_cast<char*>(dV), static_cast<char*>(dK), pace};
+        dim3 grid(2u * ((units + 7u) & ~7u)), block(512);
+        hipLaunchKernelGGL(attn_bwd_pair_mfma_kernel, grid, block, smem, st, g, pq2, pp);
+        return hipGetLastError();
+    }
     return launch_attn_C<128>(g, pq, pv, pk, 3, st);
 }
 

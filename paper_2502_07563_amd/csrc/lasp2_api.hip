@@ -97,6 +97,12 @@ int check_ptrs(std::initializer_list<const void*> ptrs)
 
 int from_hip(hipError_t e) { return e == hipSuccess ? LASP2_OK : LASP2_ERR_LAUNCH; }
 
+// Layout of the backward's workspace: the fp32 state array [G][T_s][d][d], then one 32-bit
+// counter per (group, slot) through which the workgroups that share a slot's reads keep in
+// step (used by the matrix-core kernels only; always part of the size).
+size_t states_bytes(const Geom& g) { return (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float); }
+size_t pace_bytes(const Geom& g) { return (((size_t)g.G * (size_t)g.T_s * sizeof(unsigned)) + 15u) & ~(size_t)15u; }
+
 // anchor_start matters with decay only: states as the slot's first token sees them (backward)
 hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, float* M,
                       int anchor_start, hipStream_t st)
@@ -137,7 +143,7 @@ int plan_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const 
     // the combine is skipped.
     pl->lone = g.lone_slots != 0;
     pl->need_states = !pl->lone || pl->inclusive;
-    pl->need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    pl->need = states_bytes(g) + pace_bytes(g);
     const bool ws = workspace && pl->need_states;
     if ((!pl->lone && !P) || (ws && !*workspace)) return LASP2_ERR_NULL;   // NULL before alignment, as everywhere
     rc = check_ptrs({Q, K, V, dO, dQ, dK, dV});
@@ -161,7 +167,10 @@ int run_attn_bwd(const BwdPlan& pl, int dtype, const void* Q, const void* K, con
         e = launch_state_prefix(g, dR, dR, 1, pl.inclusive ? 1 : 0, st);
         if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     }
-    if (pl.fast) return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, dQ, dK, dV, st));
+    if (pl.fast) {
+        unsigned* pace = dR ? reinterpret_cast<unsigned*>(reinterpret_cast<char*>(dR) + states_bytes(g)) : nullptr;
+        return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, pace, dQ, dK, dV, st));
+    }
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
     // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
     e = launch_attn_generic(g, dtype, dO, V, K, P, dQ, 1, 0, st);
@@ -217,7 +226,7 @@ int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes)
     bool empty = false;
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
-    *bytes = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
+    *bytes = states_bytes(g) + pace_bytes(g);
     return LASP2_OK;
 }
 
@@ -338,8 +347,7 @@ int lasp2_nomask_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, con
     if (empty) return LASP2_OK;
     rc = check_ptrs({Q, K, V, dO, S, dQ, dK, dV, workspace});
     if (rc != LASP2_OK) return rc;
-    size_t need = (size_t)g.G * (size_t)g.T_s * (size_t)g.d * (size_t)g.d * sizeof(float);
-    if (workspace_bytes < need) return LASP2_ERR_WORKSPACE;
+    if (workspace_bytes < states_bytes(g) + pace_bytes(g)) return LASP2_ERR_WORKSPACE;   // one size for both backward calls
 
     hipStream_t st = (hipStream_t)stream;
     float* dS = static_cast<float*>(workspace);

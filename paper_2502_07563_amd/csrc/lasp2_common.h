@@ -146,9 +146,11 @@ hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, con
 // dQ, dV, dK in one launch.  P: exclusive prefix states of K^T V (from the forward);
 // dR: INCLUSIVE suffix states of Q^T dO (slot s holds the sum over slots >= s of its document);
 // with decay: the EXCLUSIVE decayed suffix of the start-anchored states.
+// pace: NULL, or G * T_s counters of scratch (see pace_bytes) through which the workgroups that
+// share a slot's reads keep in step; the launch clears them itself.
 hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
-                                const void* dO, const float* P, const float* dR, void* dQ, void* dK,
-                                void* dV, hipStream_t st);
+                                const void* dO, const float* P, const float* dR, unsigned* pace, void* dQ,
+                                void* dK, void* dV, hipStream_t st);
 
 // Row-times-state products of the unmasked path, up to three in one launch:
 // out_i = A_i * state_i[slot] (or its transpose), i < n.

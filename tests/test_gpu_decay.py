@@ -40,8 +40,9 @@ def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None, lam=None):
     bd.lasp2_state_prefix(p, M, P, False)
     bd.lasp2_attn_fwd(p, Q, K, V, P, O)
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-    ws = torch.empty_like(M)
-    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
+    ws_all = bd.alloc_workspace(p)
+    ws = bd.workspace_states(p, ws_all)
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws_all)
     torch.cuda.synchronize()
 
     x64 = {k: v.astype(np.float64) for k, v in x.items()}

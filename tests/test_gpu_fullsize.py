@@ -39,7 +39,7 @@ def _run_config(name):
     bd.lasp2_state_prefix(p, M, P, False)
     O, dQ, dK, dV = (nan(dev["Q"]) for _ in range(4))
     bd.lasp2_attn_fwd(p, dev["Q"], dev["K"], dev["V"], P, O)
-    bd.lasp2_attn_bwd(p, dev["Q"], dev["K"], dev["V"], dev["dO"], P, dQ, dK, dV, nan(M))
+    bd.lasp2_attn_bwd(p, dev["Q"], dev["K"], dev["V"], dev["dO"], P, dQ, dK, dV, nan(bd.alloc_workspace(p)))
     dP = nan(M)
     bd.lasp2_chunk_states(p, dev["Q"], dev["dO"], dP)
     bd.lasp2_state_prefix(p, dP, dP, True)

@@ -30,8 +30,9 @@ def _run(oracle, B, H, N, d, C, L, dtype, seed, cu=None):
     M2 = M.clone()
     bd.lasp2_state_total(p, M2, M2)          # in place
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-    ws = torch.empty_like(M)
-    bd.lasp2_nomask_bwd(p, Q, K, V, dO, S, dQ, dK, dV, ws)
+    ws_all = bd.alloc_workspace(p)
+    ws = bd.workspace_states(p, ws_all)
+    bd.lasp2_nomask_bwd(p, Q, K, V, dO, S, dQ, dK, dV, ws_all)
     torch.cuda.synchronize()
     assert torch.equal(M2, S)
 

@@ -45,7 +45,7 @@ def _run_all(oracle, B, H, N, d, C, L, dtype, seed, cu=None, check_bwd=True):
 
     if check_bwd:
         dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-        ws = torch.empty_like(M)
+        ws = bd.alloc_workspace(p)
         bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, ws)
         torch.cuda.synchronize()
         dQ_ref, dK_ref, dV_ref = oracle.bwd_def(x64["Q"], x64["K"], x64["V"], x64["dO"], cu)
@@ -122,7 +122,7 @@ def test_slot_lengths_around_block_and_half_boundaries(oracle, decay):
     bd.lasp2_chunk_states(p, K, V, M)
     bd.lasp2_state_prefix(p, M, P, False)
     bd.lasp2_attn_fwd(p, Q, K, V, P, O)
-    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, torch.empty_like(M))
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, bd.alloc_workspace(p))
     torch.cuda.synchronize()
     x64 = {k: v.astype(np.float64) for k, v in x.items()}
     if decay:

@@ -97,7 +97,10 @@ def test_no_compiler_placed_vmcnt_wait_in_the_walk(isa):
                 assert in_asm, (cname, i, l.strip())
 
 
-SKEW = ("attn_skew_mfma_kernelILb0E", "attn_skew_mfma_kernelILb1E")     # without / with decay
+# (symbol fragment, number of walk copies in the function): attn_skew_mfma_kernel without / with decay
+# (two halves x two directions), and the backward's launch for long slots (four copies of the
+# anti-causal pair's walk: dV / dK rows x early / late row blocks, plus the causal walk's two halves)
+SKEW = (("attn_skew_mfma_kernelILb0E", 4), ("attn_skew_mfma_kernelILb1E", 4), ("attn_bwd_pair_mfma_kernel", 6))
 
 
 def _skew_blocks(lines, inst):
@@ -118,15 +121,15 @@ def _skew_blocks(lines, inst):
     return lines[start:end], blocks
 
 
-@pytest.mark.parametrize("inst", SKEW)
-def test_skew_kernel_uses_no_scratch_and_waits_only_where_it_says(isa, inst):
-    """attn_skew_mfma_kernel (four copies of the walk in one function): no scratch memory, and inside
-    its loops no vector-memory wait placed by the compiler (the prologues, outside the loops, wait for
-    the slot state with ordinary loads)."""
+@pytest.mark.parametrize("inst,ncopies", SKEW)
+def test_skew_kernel_uses_no_scratch_and_waits_only_where_it_says(isa, inst, ncopies):
+    """attn_skew_mfma_kernel and attn_bwd_pair_mfma_kernel (several copies of a walk in one function):
+    no scratch memory, and inside the walks' loops no vector-memory wait placed by the compiler (the
+    prologues, outside the loops, wait for the slot state with ordinary loads)."""
     body, blocks = _skew_blocks(isa, inst)
-    assert not any("scratch_" in l for l in body), "attn_skew_mfma_kernel touches scratch memory"
+    assert not any("scratch_" in l for l in body), f"{inst} touches scratch memory"
     loops = {h for h, ins in blocks if h and any("v_mfma" in l for l in ins)}
-    assert len(loops) == 4, loops            # one walk per half and direction
+    assert len(loops) == ncopies, loops            # one loop per copy of a walk
     for h, ins in blocks:
         if h not in loops:
             continue
@@ -140,8 +143,8 @@ def test_skew_kernel_uses_no_scratch_and_waits_only_where_it_says(isa, inst):
                 assert in_asm, (h, l.strip())
 
 
-@pytest.mark.parametrize("inst", SKEW)
-def test_skew_kernel_leaves_the_rows_in_flight_alone(isa, inst):
+@pytest.mark.parametrize("inst,ncopies", SKEW)
+def test_skew_kernel_leaves_the_rows_in_flight_alone(isa, inst, ncopies):
     """The rows of A are requested with asm loads one or two blocks before they are needed, and taken
     over by an OR with the zero that the counted wait returns.  Between the request and that OR no
     instruction may touch the 32 destination registers (a copy made while a load is on its way
@@ -184,7 +187,7 @@ def test_skew_kernel_leaves_the_rows_in_flight_alone(isa, inst):
             for i in r:
                 assert not (_regs(code[i][0]) & dest), (h, code[i][0])
         checked += 1
-    assert checked == 4
+    assert checked == ncopies
     # requests before the loops (the first half's walks): nothing touches their registers until the wait
     in_asm, pending = False, None
     for h, ins in blocks:
