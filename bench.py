@@ -31,10 +31,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 #   traffic_*_bytes: HBM bytes per launch of the attention kernel, FETCH_SIZE + WRITE_SIZE
 #                    (profiles/lasp2_kernels_cfg3_hbm_traffic.txt)
 #   mfma_insts_*:    v_mfma_f32_32x32x16_bf16 instructions per launch, SQ_INSTS_MFMA
-#                    (profiles/attn_skew_mfma_kernel_cfg3_sq_counters.txt)
+#                    (profiles/attn_kernels_cfg3_sq_counters.txt)
 PROFILE_CONSTANTS = {
-    "cfg3": {"traffic_fwd_bytes": 4.363e9, "traffic_bwd_bytes": 8.560e9,
-             "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 41025536},
+    "cfg3": {"traffic_fwd_bytes": 4.3626e9, "traffic_bwd_bytes": 7.7480e9,
+             "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 32636928},
 }
 MFMA_FLOP = 2 * 32 * 32 * 16    # one v_mfma_f32_32x32x16_bf16
 
@@ -286,16 +286,17 @@ def main():
     seg = {n: stat(v) for n, v in zip(seg_names, per_step)}
 
     esz = 2 if dtype == "bf16" else 4
-    # Dominant kernel: the fused attention pass, launched twice per step.  Algorithmic bytes:
+    mfma_path = dtype == "bf16" and d == 128
+    pair_kernel = mfma_path and (L or C) > 128 and not args.decay   # dV and dK of a slot in one workgroup
+    # Dominant kernels: the attention launches, one per direction.  Algorithmic bytes:
     #   forward launch : Q, K, V read, O written, one state array read            (4 passes)
-    #   backward launch: Q, K, V, dO read once, dQ, dK, dV written, P read once and the suffix
-    #                    states twice (dV and dK each read them)                   (7 passes)
-    # With one slot per sequence no prefix state is read (forward: none; backward: the slots' own
-    # dM_t twice).
+    #   backward launch: Q, K, V, dO read once, dQ, dK, dV written, P read once and the suffix states
+    #                    once (dV and dK in one workgroup) or twice (one workgroup each)   (7 passes)
+    # With one slot per sequence no prefix state is read.
     tensor = B * H * N * d * esz
     states = B * H * T_s * d * d * 4
     bytes_fwd = 4 * tensor + (0 if lone else states)
-    bytes_bwd = 7 * tensor + (2 if lone else 3) * states
+    bytes_bwd = 7 * tensor + ((0 if lone else 1) + (1 if pair_kernel else 2)) * states
     # HIP events bracket the forward launch exactly.  The backward launch sits inside
     # lasp2_attn_bwd behind a states kernel and a combine kernel that are the same launches as
     # the step's chunk_states / state_prefix segments (timed once before the loop when the step
@@ -306,11 +307,14 @@ def main():
         pre = [a + b for a, b in zip(per_step[0], per_step[1])]
     fwd_v = per_step[seg_names.index("attn_fwd")]
     bwd_v = [t - q for t, q in zip(per_step[seg_names.index("attn_bwd")], pre)]
-    mfma_path = dtype == "bf16" and d == 128
-    kern = ("attn_generic_kernel" if not mfma_path else
-            ("attn_skew_mfma_kernel" if (L or C) > 128 else ("attn_decay_mfma_kernel<128>" if args.decay else "attn_mfma_kernel<128>")))
-    if args.decay and mfma_path and (L or C) > 128:
-        kern += "<decay>"
+    wide = (L or C) > 128
+    if not mfma_path:
+        kern_fwd = kern_bwd = "attn_generic_kernel"
+    elif args.decay:
+        kern_fwd = kern_bwd = "attn_skew_mfma_kernel<decay>" if wide else "attn_decay_mfma_kernel<128>"
+    else:
+        kern_fwd = "attn_skew_mfma_kernel" if wide else "attn_mfma_kernel<128>"
+        kern_bwd = "attn_bwd_pair_mfma_kernel" if wide else "attn_mfma_kernel<128>"
     consts = {} if (args.decay or args.slot_len is not None) else PROFILE_CONSTANTS.get(args.workload, {})
 
     def launch(v, nbytes, traffic):
@@ -321,8 +325,8 @@ def main():
     lf = launch(fwd_v, bytes_fwd, consts.get("traffic_fwd_bytes"))
     lb = launch(bwd_v, bytes_bwd, consts.get("traffic_bwd_bytes"))
     # the headline is the longer launch's own figure, not a blend of the two
-    head, which = (lb, "backward launch (the dQ, dV, dK problems of every slot in one launch)") \
-        if lb["ms"] >= lf["ms"] else (lf, "forward launch")
+    head, which = (lb, f"{kern_bwd}, the backward's attention launch (dQ, dV, dK of every slot)") \
+        if lb["ms"] >= lf["ms"] else (lf, f"{kern_fwd}, the forward's attention launch")
     flops_nominal = nominal_flops_per_token_head(d, C) * tokens * H
     out = {
         "metric": "fwd+bwd tokens/s per layer",
@@ -338,10 +342,10 @@ def main():
         "ms_median": {n: seg[n]["median"] for n in seg_names},
         "ms_min": {n: seg[n]["min"] for n in seg_names},
         "mfma_frac_nominal": flops_nominal / (dt / args.steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
-        "roofline": {"bound": "hbm", "kernel": f"{kern}, {which}: the longer of its two launches per step",
+        "roofline": {"bound": "hbm", "kernel": f"{which}: the longer of the step's two attention launches",
                      "achieved": head["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["frac"], "traffic": head["traffic"],
-                     "launch_ms": head["ms"], "launches": {"fwd": lf, "bwd": lb},
+                     "launch_ms": head["ms"], "launches": {"fwd": dict(lf, kernel=kern_fwd), "bwd": dict(lb, kernel=kern_bwd)},
                      "device_copy_GBps": copy_gbps},
     }
     if "mfma_insts_fwd" in consts:

@@ -2185,7 +2185,7 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
         if (pace) {
             hipLaunchKernelGGL(zero_u32_kernel, dim3((units + 255u) / 256u), dim3(256), 0, st, pace, units);
             pq2.pace = pace;
-            pq2.lead = 0;
+            pq2.lead = 0;   // (leads of -1 .. 2 blocks measured alike)
         }
         const PairProblem pp = {static_cast<const char*>(Q), static_cast<const char*>(dO),
                                 static_cast<const char*>(K), static_cast<const char*>(V), dR,

@@ -45,6 +45,6 @@ def test_counter_figures_in_bench_match_the_committed_profile_summaries():
     # the summaries print GiB with three decimals
     assert abs(consts["traffic_fwd_bytes"] - fwd * GiB) <= 0.001 * GiB
     assert abs(consts["traffic_bwd_bytes"] - bwd * GiB) <= 0.001 * GiB
-    text = open(os.path.join(ROOT, "profiles", "attn_skew_mfma_kernel_cfg3_sq_counters.txt")).read()
+    text = open(os.path.join(ROOT, "profiles", "attn_kernels_cfg3_sq_counters.txt")).read()
     assert consts["mfma_insts_fwd"] == int(re.search(r"forward\s+SQ_INSTS_MFMA\s+(\d+)", text).group(1))
     assert consts["mfma_insts_bwd"] == int(re.search(r"backward\s+SQ_INSTS_MFMA\s+(\d+)", text).group(1))
