@@ -168,6 +168,9 @@ def main():
                          "(default: the queries are the whole sequence)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=131072)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step into a HIP graph and time its replays (added as "
+                         "`graph_ms_per_step`; `value` stays the eager step's)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="kept for older command lines: the 1 GiB device-to-device copy (outside the timed "
                          "region) that a counter run scales its counters by is now always run")
@@ -277,6 +280,23 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    graph_ms = None
+    if args.graph:
+        # The library only enqueues kernels on the caller's stream, so the step records as it stands.
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            step(False)
+        for _ in range(max(1, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+
     ms_per_step = dt * 1e3 / args.steps
     tokens = B * N
     value = tokens / (dt / args.steps)
@@ -348,6 +368,8 @@ def main():
                      "launch_ms": head["ms"], "launches": {"fwd": dict(lf, kernel=kern_fwd), "bwd": dict(lb, kernel=kern_bwd)},
                      "device_copy_GBps": copy_gbps},
     }
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = graph_ms
     if "mfma_insts_fwd" in consts:
         # executed matrix-core work: the attention launches from the SQ_INSTS_MFMA counter, the two
         # chunk-state launches from their tiling (2 d^2 flop per token and head, no padding at this size)
