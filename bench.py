@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 #   mfma_insts_*:    v_mfma_f32_32x32x16_bf16 instructions per launch, SQ_INSTS_MFMA
 #                    (profiles/attn_kernels_cfg3_sq_counters.txt)
 PROFILE_CONSTANTS = {
-    "cfg3": {"traffic_fwd_bytes": 4.3626e9, "traffic_bwd_bytes": 7.7480e9,
+    "cfg3": {"traffic_fwd_bytes": 4.3626e9, "traffic_bwd_bytes": 7.7487e9,
              "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 32636928},
 }
 MFMA_FLOP = 2 * 32 * 32 * 16    # one v_mfma_f32_32x32x16_bf16
@@ -155,6 +155,9 @@ def main():
     ap.add_argument("--slot-len", type=int, default=None,
                     help="tokens per state slot L (a multiple of C) instead of the workload's own; "
                          "L = N is the serial-carry schedule with one slot per head")
+    ap.add_argument("--heads", type=int, default=None,
+                    help="override the workload's number of heads (a study of a partly filled device; "
+                         "such a line is not the named workload and carries no profile constants)")
     ap.add_argument("--decay", action="store_true",
                     help="run the step with scalar decay, per-head factors 1 - 2^(-5-h) (not the headline "
                          "workload; the CPU baseline, which is the undecayed oracle, is then left out)")
@@ -191,6 +194,8 @@ def main():
     B, H, N, d, C, L = (cfg[k] for k in ("B", "H", "N", "d", "C", "L"))
     if args.slot_len is not None:
         L = args.slot_len
+    if args.heads is not None:
+        H = args.heads
     dtype = cfg["dtype"]
     cu = synth.config_offsets(cfg)
     dev = torch.device("cuda:0")
@@ -335,7 +340,7 @@ def main():
     else:
         kern_fwd = "attn_skew_mfma_kernel" if wide else "attn_mfma_kernel<128>"
         kern_bwd = "attn_bwd_pair_mfma_kernel" if wide else "attn_mfma_kernel<128>"
-    consts = {} if (args.decay or args.slot_len is not None) else PROFILE_CONSTANTS.get(args.workload, {})
+    consts = {} if (args.decay or args.slot_len is not None or args.heads is not None) else PROFILE_CONSTANTS.get(args.workload, {})
 
     def launch(v, nbytes, traffic):
         st = stat(v)
