@@ -82,6 +82,18 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     g->n_seqs = desc->n_seqs;
     g->lone_slots = (T_s == (desc->n_seqs > 0 ? (int64_t)desc->n_seqs : (int64_t)1)) ? 1 : 0;
     g->cu = desc->cu_seqlens_dev;
+    // marks for slot_range: the number of slots before every doc_stride-th document
+    g->doc_stride = 1;
+    for (int j = 0; j < kDocMarks; ++j) g->doc_mark[j] = j == 0 ? 0 : INT32_MAX;
+    if (desc->n_seqs > 0) {
+        const int32_t* cu = desc->cu_seqlens_host;
+        g->doc_stride = (desc->n_seqs + kDocMarks - 1) / kDocMarks;
+        int64_t before = 0;
+        for (int k = 0; k < desc->n_seqs; ++k) {
+            if (k % g->doc_stride == 0) g->doc_mark[k / g->doc_stride] = (int32_t)before;
+            before += ((int64_t)(cu[k + 1] - cu[k]) + L - 1) / L;
+        }
+    }
     *empty = (G == 0 || desc->N == 0);
     return LASP2_OK;
 }

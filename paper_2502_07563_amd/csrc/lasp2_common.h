@@ -11,6 +11,8 @@
 
 namespace lasp2 {
 
+constexpr int kDocMarks = 32;
+
 // Problem geometry handed by value to every kernel.
 struct Geom {
     int32_t G;            // B*H independent (batch, head) groups
@@ -23,6 +25,11 @@ struct Geom {
     int32_t lone_slots;   // host decision: every document (sequence) is a single slot, so every
                           // exclusive prefix and suffix state is zero
     const int32_t* cu;    // packed: DEVICE pointer to n_seqs+1 offsets
+    // packed: slots that lie before document j * doc_stride, j = 0 .. kDocMarks-1, filled on the
+    // host (INT32_MAX past the last document): a kernel finds the document of a slot from the
+    // nearest mark instead of counting from the first document
+    int32_t doc_stride;
+    int32_t doc_mark[kDocMarks];
     int32_t H;            // heads (group g uses decay[g % H])
     const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
     int32_t decay_mfma;   // host decision: every factor is large enough for the MFMA decay kernels
@@ -39,8 +46,9 @@ __device__ __forceinline__ float decay_log2(const Geom& g, int grp)
     return g.decay ? log2f(g.decay[grp % g.H]) : 0.f;
 }
 
-// Token range [tok0, tok0+len) of slot s.  Unpacked: direct.  Packed: walk the
-// documents (uniform scalar loads; n_seqs is small next to the work per slot).
+// Token range [tok0, tok0+len) of slot s.  Unpacked: direct.  Packed: from the last host-made
+// mark at or before s, then document by document (at most doc_stride of them; uniform scalar
+// loads).  Document lengths and L are below 2^31, so the slot counts are 32-bit divisions.
 __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int& len)
 {
     if (g.n_seqs == 0) {
@@ -51,16 +59,20 @@ __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int&
         len = (int)(b - a);
         return;
     }
-    int base = 0;
+    int j = 0;
+#pragma unroll
+    for (int step = kDocMarks / 2; step >= 1; step >>= 1)
+        if (g.doc_mark[j + step] <= s) j += step;
+    int base = g.doc_mark[j];
+    const uint32_t L = (uint32_t)min(g.L, (int64_t)INT32_MAX);   // a longer slot holds any document whole
     tok0 = 0;
     len = 0;
-    for (int k = 0; k < g.n_seqs; ++k) {
-        int a = g.cu[k], b = g.cu[k + 1];
-        int ns = (int)(((int64_t)(b - a) + g.L - 1) / g.L);
+    for (int k = j * g.doc_stride; k < g.n_seqs; ++k) {
+        const int a = g.cu[k], b = g.cu[k + 1];
+        const int ns = (int)(((uint32_t)(b - a) + (L - 1u)) / L);
         if (s < base + ns) {
-            int64_t t0 = (int64_t)a + (int64_t)(s - base) * g.L;
-            int64_t t1 = t0 + g.L;
-            if (t1 > b) t1 = b;
+            const int64_t t0 = (int64_t)a + (int64_t)(s - base) * L;
+            const int64_t t1 = min(t0 + (int64_t)L, (int64_t)b);
             tok0 = (int)t0;
             len = (int)(t1 - t0);
             return;

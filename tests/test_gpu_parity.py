@@ -96,6 +96,19 @@ def test_packed_documents(oracle, dtype, d, C, L):
     _run_all(oracle, 1, 2, int(cu[-1]), d, C, L, dtype, seed=40, cu=cu)
 
 
+@pytest.mark.parametrize("dtype,d,C,L,ndocs", [("bf16", 128, 64, 64, 33), ("bf16", 128, 128, 256, 150),
+                                               ("f32", 32, 32, 64, 97)])
+def test_many_documents(oracle, dtype, d, C, L, ndocs):
+    """More documents than the kernels keep marks for (32): the slot -> document search starts from
+    a mark and walks on; lengths from 1 token to a few slots, so documents of one and of several
+    slots alternate."""
+    rng = np.random.default_rng(1000 + ndocs)
+    lens = rng.integers(1, 3 * L + 2, size=ndocs)
+    lens[::7] = 1
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _run_all(oracle, 1, 2, int(cu[-1]), d, C, L, dtype, seed=45, cu=cu)
+
+
 @pytest.mark.parametrize("decay", [False, True])
 def test_slot_lengths_around_block_and_half_boundaries(oracle, decay):
     """One slot per document, lengths on both sides of every 64-token block boundary of the 256-row
