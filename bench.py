@@ -219,7 +219,6 @@ def main():
     # One slot per sequence (e.g. --slot-len N): the serial-carry schedule.  Every prefix is zero, so
     # the step makes no chunk_states / state_prefix call and hands P = NULL to both attention calls.
     lone = T_s == (1 if cu is None else len(cu) - 1)
-    bwd_runs_states = lone and dtype == "bf16" and d == 128 and not args.decay
     seg_names = ["attn_fwd", "attn_bwd"] if lone else ["chunk_states", "state_prefix", "attn_fwd", "attn_bwd"]
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -247,18 +246,35 @@ def main():
         if record:
             marks.append(e)
 
-    states_ms = 0.0
-    if bwd_runs_states:
-        # what lasp2_attn_bwd spends on the slots' own dM_t before its attention launch
-        bd.lasp2_chunk_states(p, Q, dO, ws)
+    # The attention kernels may walk several of the caller's slots per workgroup (lasp2_walk_slots):
+    # the forward then reads one prefix state per walk, and the backward builds its dM states per walk.
+    Leff = L or C
+    doc_lens = [N] if cu is None else [int(b - a) for a, b in zip(cu[:-1], cu[1:])]
+    walks = lambda w: sum(-(-n // (w * Leff)) for n in doc_lens)
+    ws_f, ws_b = bd.lasp2_walk_slots(p), bd.lasp2_walk_slots(p, backward=True)
+    Tw_f, Tw_b = walks(ws_f), walks(ws_b)
+    lone_f, lone_b = Tw_f == len(doc_lens), Tw_b == len(doc_lens)
+    # What lasp2_attn_bwd spends before its attention launch: the walks' own dM_t = Q_t^T dO_t and their
+    # suffix combine, timed once here through the public calls on a descriptor whose slots are the walks
+    # (the undecayed matrix-core kernels want the dM_t even when every sequence is a single walk).
+    pre_ms = 0.0
+    mfma = dtype == "bf16" and d == 128
+    if not lone_b or (mfma and not args.decay):
+        pw = bd.Problem(B, H, N, d, C, ws_b * Leff, dtype, cu, decay=decay) if ws_b > 1 else p
+
+        def pre():
+            bd.lasp2_chunk_states(pw, Q, dO, ws)
+            if not lone_b:
+                bd.lasp2_state_prefix(pw, ws, ws, True)
+        pre()
         torch.cuda.synchronize()
         c0, c1 = ev(), ev()
         c0.record()
         for _ in range(5):
-            bd.lasp2_chunk_states(p, Q, dO, ws)
+            pre()
         c1.record()
         torch.cuda.synchronize()
-        states_ms = c0.elapsed_time(c1) / 5
+        pre_ms = c0.elapsed_time(c1) / 5
 
     # A plain 1 GiB device-to-device copy, outside the timed region: what a streaming kernel
     # reaches on this device next to the published peak (and, under a counter run, a kernel
@@ -312,34 +328,30 @@ def main():
 
     esz = 2 if dtype == "bf16" else 4
     mfma_path = dtype == "bf16" and d == 128
-    pair_kernel = mfma_path and (L or C) > 128 and not args.decay   # dV and dK of a slot in one workgroup
+    pair_kernel = mfma_path and ws_b * Leff > 128 and not args.decay   # dV and dK of a walk in one workgroup
     # Dominant kernels: the attention launches, one per direction.  Algorithmic bytes:
     #   forward launch : Q, K, V read, O written, one state array read            (4 passes)
     #   backward launch: Q, K, V, dO read once, dQ, dK, dV written, P read once and the suffix states
     #                    once (dV and dK in one workgroup) or twice (one workgroup each)   (7 passes)
     # With one slot per sequence no prefix state is read.
     tensor = B * H * N * d * esz
-    states = B * H * T_s * d * d * 4
-    bytes_fwd = 4 * tensor + (0 if lone else states)
-    bytes_bwd = 7 * tensor + ((0 if lone else 1) + (1 if pair_kernel else 2)) * states
+    state = B * H * d * d * 4
+    bytes_fwd = 4 * tensor + (0 if lone_f else Tw_f * state)
+    bytes_bwd = 7 * tensor + ((0 if lone_b else 1) + (1 if pair_kernel else 2)) * Tw_b * state
     # HIP events bracket the forward launch exactly.  The backward launch sits inside
-    # lasp2_attn_bwd behind a states kernel and a combine kernel that are the same launches as
-    # the step's chunk_states / state_prefix segments (timed once before the loop when the step
-    # itself has none), so its time is attn_bwd minus those.
-    if lone:
-        pre = [states_ms if bwd_runs_states else 0.0] * len(marks)
-    else:
-        pre = [a + b for a, b in zip(per_step[0], per_step[1])]
+    # lasp2_attn_bwd behind a states kernel and a combine kernel, timed before the loop (pre_ms),
+    # so its time is attn_bwd minus those.
     fwd_v = per_step[seg_names.index("attn_fwd")]
-    bwd_v = [t - q for t, q in zip(per_step[seg_names.index("attn_bwd")], pre)]
-    wide = (L or C) > 128
+    bwd_v = [t - pre_ms for t in per_step[seg_names.index("attn_bwd")]]
+    wide_f, wide_b = ws_f * Leff > 128, ws_b * Leff > 128
     if not mfma_path:
         kern_fwd = kern_bwd = "attn_generic_kernel"
     elif args.decay:
-        kern_fwd = kern_bwd = "attn_skew_mfma_kernel<decay>" if wide else "attn_decay_mfma_kernel<128>"
+        kern_fwd = "attn_skew_mfma_kernel<decay>" if wide_f else "attn_decay_mfma_kernel<128>"
+        kern_bwd = "attn_skew_mfma_kernel<decay>" if wide_b else "attn_decay_mfma_kernel<128>"
     else:
-        kern_fwd = "attn_skew_mfma_kernel" if wide else "attn_mfma_kernel<128>"
-        kern_bwd = "attn_bwd_pair_mfma_kernel" if wide else "attn_mfma_kernel<128>"
+        kern_fwd = "attn_skew_mfma_kernel" if wide_f else "attn_mfma_kernel<128>"
+        kern_bwd = "attn_bwd_pair_mfma_kernel" if wide_b else "attn_mfma_kernel<128>"
     consts = {} if (args.decay or args.slot_len is not None or args.heads is not None) else PROFILE_CONSTANTS.get(args.workload, {})
 
     def launch(v, nbytes, traffic):
@@ -362,7 +374,7 @@ def main():
                                + (f" packed {cfg['n_docs']} docs" if cu is not None else "")
                                + (" decay 1-2^(-5-h)" if args.decay else "")
                                + (" serial carry: one slot per sequence, no state arrays in the forward" if lone else ""),
-                   "state_slots": int(T_s)},
+                   "state_slots": int(T_s), "slots_per_walk": {"fwd": ws_f, "bwd": ws_b}},
         "ms": {n: seg[n]["mean"] for n in seg_names},
         "ms_median": {n: seg[n]["median"] for n in seg_names},
         "ms_min": {n: seg[n]["min"] for n in seg_names},

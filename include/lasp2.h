@@ -132,6 +132,21 @@ typedef struct lasp2_desc {
 /* Number of state slots T_s per (b,h) for this descriptor (see "Slots" above). */
 int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s);
 
+/*
+ * How many of the caller's slots one workgroup of the bf16, d = 128 attention
+ * kernels walks in one go (`backward` = 0: lasp2_attn_fwd, else lasp2_attn_bwd),
+ * 1 for every other path.  The state a fused pass carries across a slot
+ * boundary is that slot's prefix M_{1:t-1} (the recurrence the prefix sum
+ * itself follows), so a walk reads P only at its first slot and the slot length
+ * fixes the granularity of the state arrays, not the number or length of the
+ * workgroups' walks: the library picks the walk length that keeps the device's
+ * CUs busy with the fewest starts (never across a document edge).  Results are
+ * the same within the rounding order.  lasp2_attn_bwd builds its dM states per
+ * walk.  The environment variable LASP2_WALK_SLOTS (a positive integer, read at
+ * every call) overrides the choice; 1 gives one walk per slot.
+ */
+int lasp2_walk_slots(const lasp2_desc_t* desc, int backward, int64_t* slots_per_walk);
+
 /* Bytes of device scratch lasp2_attn_bwd and lasp2_nomask_bwd need: one fp32 state array
  * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine, followed by one 32-bit
  * counter per (b,h,slot) with which the backward's workgroups that read the same slot keep in
@@ -170,6 +185,8 @@ int lasp2_state_prefix(const lasp2_desc_t* desc, const float* M, float* P,
  * where M_{1:t-1} = P[slot] + the states of the slot's earlier chunks (carried
  * on chip).  In: Q,K,V [B,H,N,d]; P [B,H,T_s,d,d] fp32 from lasp2_state_prefix
  * (reverse = 0).  Out: O [B,H,N,d] in `dtype`, written once.
+ * Every entry of P must be valid, but not every entry is necessarily read
+ * (see lasp2_walk_slots).
  * P may be NULL when every sequence (document) is a single slot: its prefix is
  * zero, the slot starts from a zero state (serial-carry schedule).  With more
  * than one slot in some sequence a NULL P is LASP2_ERR_NULL.

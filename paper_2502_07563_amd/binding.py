@@ -52,6 +52,7 @@ def lib():
         dp = ctypes.POINTER(Desc)
         L.lasp2_num_slots.argtypes = [dp, i64p]
         L.lasp2_workspace_size.argtypes = [dp, szp]
+        L.lasp2_walk_slots.argtypes = [dp, ctypes.c_int, i64p]
         L.lasp2_chunk_states.argtypes = [dp, vp, vp, vp, vp]
         L.lasp2_state_prefix.argtypes = [dp, vp, vp, ctypes.c_int, vp]
         L.lasp2_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp]
@@ -69,7 +70,7 @@ def lib():
         L.lasp2_softmax_bwd_share.argtypes = [dp, i64, i64] + [vp] * 10 + [ctypes.c_size_t, ctypes.c_int, vp]
         L.lasp2_status_string.argtypes = [ctypes.c_int]
         L.lasp2_status_string.restype = ctypes.c_char_p
-        for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_chunk_states",
+        for name in ("lasp2_num_slots", "lasp2_workspace_size", "lasp2_walk_slots", "lasp2_chunk_states",
                      "lasp2_state_prefix", "lasp2_attn_fwd", "lasp2_attn_bwd", "lasp2_attn_bwd_noalloc",
                      "lasp2_state_total",
                      "lasp2_nomask_fwd", "lasp2_nomask_bwd", "lasp2_softmax_fwd",
@@ -166,6 +167,12 @@ def _stream(stream):
 def lasp2_num_slots(p: Problem) -> int:
     out = ctypes.c_int64(0)
     _check(lib().lasp2_num_slots(p.ref, ctypes.byref(out)), "lasp2_num_slots")
+    return out.value
+
+
+def lasp2_walk_slots(p: Problem, backward=False) -> int:
+    out = ctypes.c_int64(0)
+    _check(lib().lasp2_walk_slots(p.ref, 1 if backward else 0, ctypes.byref(out)), "lasp2_walk_slots")
     return out.value
 
 

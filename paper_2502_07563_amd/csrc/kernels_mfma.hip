@@ -311,12 +311,21 @@ struct AttnProblem {
     const char* Bk;       // rows scored against A
     const char* Cv;       // rows mixed by the scores
     const float* state;   // [G][T_s][d][d] slot states (see `anti`)
+    int user_state;       // `state` is the caller's array, one entry per slot of the CALLER's length (Geom: P_Ts, wslots)
     char* out;
     int transpose_state;  // read the d x d slot state transposed
     int anti;             // 0: causal (j <= i); 1: anti-causal (j >= i)
     const unsigned* pace; // NULL, or per (group, slot): 64-token blocks another workgroup has begun
     int lead;             // with pace: this walk may be at most `lead` blocks ahead of that count
 };
+
+// The d x d state a walk starts from: entry `s` of an array with one state per walk, or, in the
+// caller's own array, the entry of the caller's slot that starts where the walk starts.
+__device__ __forceinline__ const float* walk_state(const Geom& g, const AttnProblem& pr, int grp, int s, int ps)
+{
+    const size_t i = pr.user_state ? (size_t)grp * g.P_Ts + ps : (size_t)grp * g.T_s + s;
+    return pr.state + i * (size_t)(D * D);
+}
 
 // Holds wave 0 of a walk (and with it, at the next barrier, its workgroup) until the workgroup it
 // shares its reads with has begun block `need`, so that the two stay within reach of each other
@@ -462,8 +471,8 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
     char* __restrict__ out = pr.out;
     const int transpose_state = pr.transpose_state;
     const int anti = pr.anti;
-    int tok0, len;
-    slot_range(g, s, tok0, len);
+    int tok0, len, ps;
+    slot_range(g, s, tok0, len, ps);
     if (len <= 0) return;
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
 
@@ -490,7 +499,7 @@ __global__ __launch_bounds__(C * 2) void attn_mfma_kernel(Geom g, AttnProblem p0
 #pragma unroll
         for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
     if (state) {   // NULL: every slot opens its document and starts from a zero state
-        const float* st = state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+        const float* st = walk_state(g, pr, grp, s, ps);
         const float sg = anti ? -1.f : 1.f;
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
@@ -747,7 +756,7 @@ __device__ __forceinline__ uint32_t wait_vmcnt_token_le(int n)
 // time (wait_vmcnt_le).
 template <bool HC1, bool ANTI, bool DECAY>
 __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, char* smem, int tid, int w,
-                                          int rb, int grp, int s, int tok0, int len)
+                                          int rb, int grp, int s, int tok0, int len, const float* wstate)
 {
     constexpr int C = 256, NW = 8, TPW = 2, BPC = 4, DPS = 4, NOP = 4;
     // With decay the anti-causal problems walk the slot backwards from the exclusive suffix (see
@@ -796,8 +805,8 @@ __device__ __forceinline__ void skew_walk(const Geom& g, const AttnProblem& pr, 
     for (int u = 0; u < TPW; ++u)
 #pragma unroll
         for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
-    if (pr.state) {   // NULL: every slot opens its document and starts from a zero state
-        const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+    if (wstate) {   // NULL: every slot opens its document and starts from a zero state
+        const float* st = wstate;
         const float sg = ENDSTATE ? -1.f : 1.f;
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
@@ -1192,16 +1201,17 @@ __global__ __launch_bounds__(512) void attn_skew_mfma_kernel(Geom g, AttnProblem
     if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
     const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
     const AttnProblem& pr = prob == 0 ? p0 : (prob == 1 ? p1 : p2);
-    int tok0, len;
-    slot_range(g, s, tok0, len);
+    int tok0, len, ps;
+    slot_range(g, s, tok0, len, ps);
     if (len <= 0) return;
+    const float* wstate = pr.state ? walk_state(g, pr, grp, s, ps) : nullptr;
     const int rb = w < 4 ? w : 11 - w;   // waves w and w+4 share a SIMD: row blocks s and 7-s
     if (rb < 4) {
-        if (pr.anti) skew_walk<false, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
-        else skew_walk<false, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        if (pr.anti) skew_walk<false, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len, wstate);
+        else skew_walk<false, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len, wstate);
     } else {
-        if (pr.anti) skew_walk<true, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
-        else skew_walk<true, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len);
+        if (pr.anti) skew_walk<true, true, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len, wstate);
+        else skew_walk<true, false, DECAY>(g, pr, smem, tid, w, rb, grp, s, tok0, len, wstate);
     }
 }
 
@@ -1619,8 +1629,8 @@ __global__ __launch_bounds__(512) void attn_bwd_pair_mfma_kernel(Geom g, AttnPro
     const int prob = (int)(blockIdx.x >> 3) & 1;
     if (unit >= (unsigned)g.T_s * (unsigned)g.G) return;
     const int s = (int)(unit % (unsigned)g.T_s), grp = (int)(unit / (unsigned)g.T_s);
-    int tok0, len;
-    slot_range(g, s, tok0, len);
+    int tok0, len, ps;
+    slot_range(g, s, tok0, len, ps);
     if (len <= 0) return;
     if (prob == 0) {
         // waves s and s+4 share a SIMD: row block s for dV, 3-s for dK
@@ -1630,8 +1640,9 @@ __global__ __launch_bounds__(512) void attn_bwd_pair_mfma_kernel(Geom g, AttnPro
         else pair_walk<true, false>(g, pp, smem, tid, w, 7 - w, grp, s, tok0, len);
     } else {
         const int rb = w < 4 ? w : 11 - w;
-        if (rb < 4) skew_walk<false, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len);
-        else skew_walk<true, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len);
+        const float* wstate = pq.state ? walk_state(g, pq, grp, s, ps) : nullptr;
+        if (rb < 4) skew_walk<false, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len, wstate);
+        else skew_walk<true, false, false>(g, pq, smem, tid, w, rb, grp, s, tok0, len, wstate);
     }
 }
 
@@ -1669,12 +1680,12 @@ hipError_t launch_attn_skew(const Geom& g, const AttnProblem& p0, const AttnProb
 // Internal chunk of the fused pass: 256 rows (eight waves) unless no slot is longer than 128.
 bool wide_chunks(const Geom& g) { return g.L > 128; }
 
-AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const float* state, void* out,
-                         int transpose_state, int anti)
+AttnProblem make_problem(const void* A, const void* Bk, const void* Cv, const float* state, int user_state,
+                         void* out, int transpose_state, int anti)
 {
     return AttnProblem{static_cast<const char*>(A), static_cast<const char*>(Bk),
-                       static_cast<const char*>(Cv), state, static_cast<char*>(out), transpose_state,
-                       anti, nullptr, 0};
+                       static_cast<const char*>(Cv), state, user_state, static_cast<char*>(out),
+                       transpose_state, anti, nullptr, 0};
 }
 
 // =====================================================================================
@@ -1720,8 +1731,8 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
     const char* __restrict__ Cv = pr.Cv;
     char* __restrict__ out = pr.out;
     const bool rev = pr.anti != 0;
-    int tok0, len;
-    slot_range(g, s, tok0, len);
+    int tok0, len, ps;
+    slot_range(g, s, tok0, len, ps);
     if (len <= 0) return;
     const size_t row0 = ((size_t)grp * g.N + tok0) * ROWB;
     const float l2 = uniform_f32(decay_log2(g, grp));   // one value per workgroup: scalar
@@ -1749,7 +1760,7 @@ __global__ __launch_bounds__(C * 2) void attn_decay_mfma_kernel(Geom g, AttnProb
 #pragma unroll
         for (int v = 0; v < 16; ++v) Macc[u][v] = 0.f;
     if (pr.state) {   // NULL: every slot opens its document and starts from a zero state
-        const float* st = pr.state + ((size_t)grp * g.T_s + s) * (size_t)(D * D);
+        const float* st = walk_state(g, pr, grp, s, ps);
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
             const int t = t0 + u, a = t >> 2, b = t & 3;
@@ -2155,7 +2166,7 @@ hipError_t launch_attn_decay(const Geom& g, const AttnProblem& p0, const AttnPro
 hipError_t launch_attn_fwd_mfma(const Geom& g, const void* Q, const void* K, const void* V,
                                 const float* P, void* O, hipStream_t st)
 {
-    const AttnProblem p = make_problem(Q, K, V, P, O, 0, 0);
+    const AttnProblem p = make_problem(Q, K, V, P, 1, O, 0, 0);
     if (g.decay) return launch_attn_decay(g, p, p, p, 1, st);
     if (wide_chunks(g)) return launch_attn_skew<false>(g, p, p, p, 1, st);
     return launch_attn_C<128>(g, p, p, p, 1, st);
@@ -2169,9 +2180,9 @@ hipError_t launch_attn_bwd_mfma(const Geom& g, const void* Q, const void* K, con
     //     cached prefix read transposed.
     // dV: anti-causal problem with (K, Q, dO); state = suffix of Q^T dO.
     // dK: anti-causal problem with (V, dO, Q); state dO^T Q = that suffix transposed.
-    const AttnProblem pq = make_problem(dO, V, K, P, dQ, 1, 0);
-    const AttnProblem pv = make_problem(K, Q, dO, dR, dV, 0, 1);
-    const AttnProblem pk = make_problem(V, dO, Q, dR, dK, 1, 1);
+    const AttnProblem pq = make_problem(dO, V, K, P, 1, dQ, 1, 0);
+    const AttnProblem pv = make_problem(K, Q, dO, dR, 0, dV, 0, 1);
+    const AttnProblem pk = make_problem(V, dO, Q, dR, 0, dK, 1, 1);
     if (g.decay) return launch_attn_decay(g, pq, pv, pk, 3, st);
     if (wide_chunks(g)) {
         constexpr int smem = 2 * NSTAGE * STAGE_BYTES + D * ROWB + 8 * 4096;

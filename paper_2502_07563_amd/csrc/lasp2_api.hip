@@ -5,6 +5,9 @@
 #include "lasp2_common.h"
 
 #include <limits.h>
+#include <stdlib.h>
+
+#include <algorithm>
 
 namespace lasp2 {
 namespace {
@@ -83,6 +86,8 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
     g->lone_slots = (T_s == (desc->n_seqs > 0 ? (int64_t)desc->n_seqs : (int64_t)1)) ? 1 : 0;
     g->cu = desc->cu_seqlens_dev;
     // marks for slot_range: the number of slots before every doc_stride-th document
+    g->wslots = 1;
+    g->P_Ts = g->T_s;
     g->doc_stride = 1;
     for (int j = 0; j < kDocMarks; ++j) g->doc_mark[j] = j == 0 ? 0 : INT32_MAX;
     if (desc->n_seqs > 0) {
@@ -94,9 +99,94 @@ int make_geom(const lasp2_desc_t* desc, Geom* g, bool* empty)
             before += ((int64_t)(cu[k + 1] - cu[k]) + L - 1) / L;
         }
     }
+    for (int j = 0; j < kDocMarks; ++j) g->doc_pmark[j] = g->doc_mark[j];
     *empty = (G == 0 || desc->N == 0);
     return LASP2_OK;
 }
+
+// ---- walks of several slots ---------------------------------------------------------------
+// The state a fused pass carries across a slot boundary IS the next slot's prefix (up to the
+// rounding order), so a workgroup may walk `ws` consecutive slots of a document and read the
+// caller's state array only at the first.  The slot length the caller chose then no longer fixes
+// how many workgroups a launch has nor how much of their time goes into starting up: one state
+// per chunk (the paper's layout) still runs with walks as long as the device can keep busy.
+
+constexpr int64_t kMaxWalkTokens = (int64_t)1 << 30;
+
+// The geometry of the walks: g with L and T_s (and the document marks) for ws slots per walk;
+// the caller's arrays stay described by P_Ts, wslots and doc_pmark.
+Geom regroup(const Geom& g, const int32_t* cu_host, int ws)
+{
+    if (ws <= 1) return g;
+    Geom w = g;
+    w.wslots = ws;
+    w.P_Ts = g.T_s;
+    w.L = g.L * ws;
+    if (g.n_seqs == 0) {
+        w.T_s = (int32_t)(((int64_t)g.N + w.L - 1) / w.L);
+        w.lone_slots = w.T_s == 1 ? 1 : 0;
+        return w;
+    }
+    int64_t walks = 0, slots = 0;
+    for (int j = 0; j < kDocMarks; ++j) w.doc_mark[j] = w.doc_pmark[j] = j == 0 ? 0 : INT32_MAX;
+    for (int k = 0; k < g.n_seqs; ++k) {
+        if (k % g.doc_stride == 0) {
+            w.doc_mark[k / g.doc_stride] = (int32_t)walks;
+            w.doc_pmark[k / g.doc_stride] = (int32_t)slots;
+        }
+        const int64_t len = cu_host[k + 1] - cu_host[k];
+        walks += (len + w.L - 1) / w.L;
+        slots += (len + g.L - 1) / g.L;
+    }
+    w.T_s = (int32_t)walks;
+    w.lone_slots = walks == g.n_seqs ? 1 : 0;
+    return w;
+}
+
+// Slots per walk for a launch that runs `par` walks at a time and gains little from walks longer
+// than `target` tokens (measured: the forward launch is flat from about 2 048 tokens on, the
+// backward from about 4 096; starting a walk costs what streaming about a hundred tokens does).
+//   - Equal sequences, enough of them to fill the device by themselves: one walk per sequence,
+//     which needs no prefix or suffix state at all (the serial-carry order of work).
+//   - Otherwise the shortest walk of at least `target` tokens (a power of two of slots), made
+//     shorter again while the launch would have fewer than two rounds of workgroups: a launch of
+//     one round ends at the pace of its slowest CU, and less than one leaves CUs without work.
+// The environment variable LASP2_WALK_SLOTS, when set to a positive number, overrides the choice
+// (for tests and tuning).
+int pick_walk_slots(const Geom& g, const int32_t* cu_host, int par, int64_t target)
+{
+    const int64_t longest_seq = [&] {
+        if (g.n_seqs == 0) return (int64_t)g.N;
+        int64_t m = 0;
+        for (int k = 0; k < g.n_seqs; ++k) m = std::max<int64_t>(m, cu_host[k + 1] - cu_host[k]);
+        return m;
+    }();
+    if (g.L >= longest_seq || g.G == 0) return 1;
+    const int64_t ws_max = std::max<int64_t>(1, std::min<int64_t>(kMaxWalkTokens / g.L, INT32_MAX / 2));
+    if (const char* e = getenv("LASP2_WALK_SLOTS")) {
+        const long v = strtol(e, nullptr, 10);
+        if (v >= 1) return (int)std::min<int64_t>(v, ws_max);
+    }
+    if (par < 1) par = 1;
+    const int64_t ws_whole = (longest_seq + g.L - 1) / g.L;   // slots of the longest sequence
+    if (g.n_seqs == 0 && ws_whole <= ws_max) {
+        const int64_t rounds = ((int64_t)g.G + par - 1) / par;
+        if ((int64_t)g.G * 100 >= rounds * par * 85) return (int)ws_whole;
+    }
+    auto units = [&](int64_t ws) {
+        const int64_t W = g.L * ws;
+        if (g.n_seqs == 0) return (int64_t)g.G * ((g.N + W - 1) / W);
+        int64_t nw = 0;
+        for (int k = 0; k < g.n_seqs; ++k) nw += ((int64_t)(cu_host[k + 1] - cu_host[k]) + W - 1) / W;
+        return (int64_t)g.G * nw;
+    };
+    int64_t ws = 1;
+    while (ws * g.L < target && ws * 2 <= ws_max && ws < ws_whole) ws *= 2;
+    while (ws > 1 && units(ws) < 2 * (int64_t)par) ws /= 2;
+    return (int)ws;
+}
+
+constexpr int64_t kWalkTargetFwd = 2048, kWalkTargetBwd = 4096;
 
 int check_ptrs(std::initializer_list<const void*> ptrs)
 {
@@ -126,13 +216,16 @@ hipError_t run_states(const Geom& g, int dtype, const void* K, const void* V, fl
 // What lasp2_attn_bwd and lasp2_attn_bwd_noalloc have in common: the checks that need no
 // workspace, and the launches.
 struct BwdPlan {
-    Geom g;
+    Geom g;             // the caller's slots (argument checks, workspace size)
+    Geom gw;            // the walks of the kernels (= g unless the matrix-core kernels take several slots per walk)
     bool empty;
     bool fast;          // matrix-core kernels
     bool inclusive;     // suffix states in the inclusive form
     bool lone;          // every document a single slot
     bool need_states;   // dM_t go through a state array of `need` bytes
     size_t need;
+    bool lone_w;        // every document a single walk
+    bool need_states_w;
 };
 
 // `workspace`: address of the caller's workspace pointer, or NULL for an entry point that has none.
@@ -161,27 +254,36 @@ int plan_attn_bwd(const lasp2_desc_t* desc, const void* Q, const void* K, const 
     rc = check_ptrs({Q, K, V, dO, dQ, dK, dV});
     if (rc != LASP2_OK) return rc;
     if ((!pl->lone && !aligned16(P)) || (ws && !aligned16(*workspace))) return LASP2_ERR_ALIGN;
+    // The kernels' own walks.  The backward's dM states live in the workspace only, so they are
+    // built per walk, not per slot of the caller: fewer of them, never more bytes than `need`.
+    pl->gw = g;
+    if (pl->fast) {
+        const int wgs = g.decay ? 3 : 2;   // workgroups per walk in the attention launch
+        pl->gw = regroup(g, desc->cu_seqlens_host, pick_walk_slots(g, desc->cu_seqlens_host, std::max(1, cu_count() / wgs), kWalkTargetBwd));
+    }
+    pl->lone_w = pl->gw.lone_slots != 0;
+    pl->need_states_w = !pl->lone_w || pl->inclusive;
     return LASP2_OK;
 }
 
 int run_attn_bwd(const BwdPlan& pl, int dtype, const void* Q, const void* K, const void* V, const void* dO,
                  const float* P, void* dQ, void* dK, void* dV, float* dR, hipStream_t st)
 {
-    const Geom& g = pl.g;
-    if (pl.lone) P = nullptr;
+    const Geom& g = pl.gw;
+    if (pl.lone_w) P = nullptr;
     hipError_t e = hipSuccess;
-    if (pl.need_states) {
-        // dM_t = Q_t^T dO_t per slot, then its suffix combine in place
+    if (pl.need_states_w) {
+        // dM_t = Q_t^T dO_t per walk, then its suffix combine in place
         e = run_states(g, dtype, Q, dO, dR, 1, st);
         if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     }
-    if (!pl.lone) {
+    if (!pl.lone_w) {
         e = launch_state_prefix(g, dR, dR, 1, pl.inclusive ? 1 : 0, st);
         if (e != hipSuccess) return LASP2_ERR_LAUNCH;
     }
     if (pl.fast) {
         unsigned* pace = dR ? reinterpret_cast<unsigned*>(reinterpret_cast<char*>(dR) + states_bytes(g)) : nullptr;
-        return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, dR, pace, dQ, dK, dV, st));
+        return from_hip(launch_attn_bwd_mfma(g, Q, K, V, dO, P, pl.need_states_w ? dR : nullptr, pace, dQ, dK, dV, st));
     }
     // dQ: the forward problem with (dO, V, K) in the roles of (Q, K, V); its state is
     // V^T K = (K^T V)^T, i.e. the cached prefix read transposed.
@@ -228,6 +330,21 @@ int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s)
     int rc = make_geom(desc, &g, &empty);
     if (rc != LASP2_OK) return rc;
     *T_s = g.T_s;
+    return LASP2_OK;
+}
+
+int lasp2_walk_slots(const lasp2_desc_t* desc, int backward, int64_t* slots_per_walk)
+{
+    if (!slots_per_walk) return LASP2_ERR_NULL;
+    Geom g;
+    bool empty = false;
+    int rc = make_geom(desc, &g, &empty);
+    if (rc != LASP2_OK) return rc;
+    *slots_per_walk = 1;
+    if (empty || !mfma_path_supported(g, desc->dtype)) return LASP2_OK;
+    const int wgs = backward ? (g.decay ? 3 : 2) : 1;
+    *slots_per_walk = pick_walk_slots(g, desc->cu_seqlens_host, std::max(1, cu_count() / wgs),
+                                      backward ? kWalkTargetBwd : kWalkTargetFwd);
     return LASP2_OK;
 }
 
@@ -281,7 +398,10 @@ int lasp2_attn_fwd(const lasp2_desc_t* desc, const void* Q, const void* K, const
     rc = (P == nullptr && g.lone_slots) ? check_ptrs({Q, K, V, O}) : check_ptrs({Q, K, V, P, O});
     if (rc != LASP2_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (mfma_path_supported(g, desc->dtype)) return from_hip(launch_attn_fwd_mfma(g, Q, K, V, P, O, st));
+    if (mfma_path_supported(g, desc->dtype)) {
+        const Geom gw = regroup(g, desc->cu_seqlens_host, pick_walk_slots(g, desc->cu_seqlens_host, cu_count(), kWalkTargetFwd));
+        return from_hip(launch_attn_fwd_mfma(gw, Q, K, V, gw.lone_slots ? nullptr : P, O, st));
+    }
     return from_hip(launch_attn_generic(g, desc->dtype, Q, K, V, P, O, 0, 0, st));
 }
 

@@ -30,6 +30,14 @@ struct Geom {
     // nearest mark instead of counting from the first document
     int32_t doc_stride;
     int32_t doc_mark[kDocMarks];
+    // The attention kernels may walk several of the caller's slots in one go (the carried state
+    // at a slot boundary is that slot's prefix, so only the first one has to be read): then L and
+    // T_s above describe the WALKS (L = wslots times the caller's slot length), and the caller's
+    // state arrays [G][P_Ts][d][d] are indexed by the walk's first slot, see slot_range.
+    // wslots = 1, P_Ts = T_s, doc_pmark = doc_mark: walks and the caller's slots are the same.
+    int32_t wslots;
+    int32_t P_Ts;
+    int32_t doc_pmark[kDocMarks];   // the caller's slots before document j * doc_stride
     int32_t H;            // heads (group g uses decay[g % H])
     const float* decay;   // DEVICE pointer to H per-head decay factors; NULL = no decay
     int32_t decay_mfma;   // host decision: every factor is large enough for the MFMA decay kernels
@@ -46,10 +54,11 @@ __device__ __forceinline__ float decay_log2(const Geom& g, int grp)
     return g.decay ? log2f(g.decay[grp % g.H]) : 0.f;
 }
 
-// Token range [tok0, tok0+len) of slot s.  Unpacked: direct.  Packed: from the last host-made
-// mark at or before s, then document by document (at most doc_stride of them; uniform scalar
-// loads).  Document lengths and L are below 2^31, so the slot counts are 32-bit divisions.
-__device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int& len)
+// Token range [tok0, tok0+len) of slot (walk) s, and ps: the index, within the group, of the
+// caller's slot that starts at tok0.  Unpacked: direct.  Packed: from the last host-made mark at
+// or before s, then document by document (at most doc_stride of them; uniform scalar loads).
+// Document lengths and L are below 2^31, so the slot counts are 32-bit divisions.
+__device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int& len, int& ps)
 {
     if (g.n_seqs == 0) {
         int64_t a = (int64_t)s * g.L;
@@ -57,16 +66,18 @@ __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int&
         if (b > g.N) b = g.N;
         tok0 = (int)a;
         len = (int)(b - a);
+        ps = s * g.wslots;
         return;
     }
     int j = 0;
 #pragma unroll
     for (int step = kDocMarks / 2; step >= 1; step >>= 1)
         if (g.doc_mark[j + step] <= s) j += step;
-    int base = g.doc_mark[j];
+    int base = g.doc_mark[j], pbase = g.doc_pmark[j];
     const uint32_t L = (uint32_t)min(g.L, (int64_t)INT32_MAX);   // a longer slot holds any document whole
     tok0 = 0;
     len = 0;
+    ps = 0;
     for (int k = j * g.doc_stride; k < g.n_seqs; ++k) {
         const int a = g.cu[k], b = g.cu[k + 1];
         const int ns = (int)(((uint32_t)(b - a) + (L - 1u)) / L);
@@ -75,10 +86,23 @@ __device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int&
             const int64_t t1 = min(t0 + (int64_t)L, (int64_t)b);
             tok0 = (int)t0;
             len = (int)(t1 - t0);
+            ps = pbase + (s - base) * g.wslots;
             return;
         }
         base += ns;
+        if (g.wslots > 1) {
+            const uint32_t Lp = L / (uint32_t)g.wslots;   // exact: L is wslots times the caller's slot length
+            pbase += (int)(((uint32_t)(b - a) + (Lp - 1u)) / Lp);
+        } else {
+            pbase += ns;
+        }
     }
+}
+
+__device__ __forceinline__ void slot_range(const Geom& g, int s, int& tok0, int& len)
+{
+    int ps;
+    slot_range(g, s, tok0, len, ps);
 }
 
 // Device ordinal of the calling thread's current device, or -1 when it cannot serve as an index

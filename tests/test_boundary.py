@@ -64,6 +64,54 @@ def test_num_slots_packed_matches_rule():
         assert _slots(d) == (0, want)
 
 
+def _walk(desc, backward=0):
+    out = ctypes.c_int64(-1)
+    rc = B.lib().lasp2_walk_slots(ctypes.byref(desc), backward, ctypes.byref(out))
+    return rc, out.value
+
+
+def test_walk_slots_choice(monkeypatch):
+    """How many of the caller's slots the matrix-core attention kernels walk at a time: the host's
+    choice (256 CUs assumed when no device answers).  One state per chunk still gives walks as long
+    as the device can keep busy; fp32, and slots that already hold a whole sequence, stay as they are."""
+    monkeypatch.delenv("LASP2_WALK_SLOTS", raising=False)
+    bf = dict(d=128, C=256, dtype=B.LASP2_BF16)
+    # 16 heads x 32 768 tokens, one state per chunk: walks of about 2 048 (forward) / 4 096 (backward)
+    # tokens, halved until the launch has two rounds of workgroups (256 forward walks at a time, 128
+    # backward ones, which take two workgroups each)
+    assert _walk(_desc(H=16, N=32768, **bf)) == (0, 4)
+    assert _walk(_desc(H=16, N=32768, **bf), 1) == (0, 8)
+    # 256 sequences of 8 192 tokens: one walk per sequence (the serial-carry order of work)
+    assert _walk(_desc(B=8, H=32, N=8192, **bf)) == (0, 32)
+    assert _walk(_desc(B=8, H=32, N=8192, **bf), 1) == (0, 32)
+    # 300 sequences would leave most CUs idle in a second round of whole sequences
+    assert _walk(_desc(B=10, H=30, N=8192, **bf)) == (0, 8)
+    # 16 heads x 262 144 tokens in 4 096-token slots: long enough as they are
+    assert _walk(_desc(H=16, N=262144, L=4096, **bf)) == (0, 1)
+    assert _walk(_desc(H=16, N=262144, L=4096, **bf), 1) == (0, 1)
+    # a launch the device runs in one go stays as it is
+    assert _walk(_desc(H=2, N=4096, **bf)) == (0, 1)
+    # fp32 takes the plain kernels: one walk per slot
+    assert _walk(_desc(H=16, N=32768)) == (0, 1)
+    # a slot that holds the whole sequence
+    assert _walk(_desc(H=16, N=4096, L=4096, **bf)) == (0, 1)
+    # packed: never longer than the longest document needs
+    cu = np.array([0, 64, 300, 301, 1024], dtype=np.int32)
+    d = _desc(H=400, N=1024, d=128, C=64, dtype=B.LASP2_BF16, n_seqs=4, cu_seqlens_host=cu.ctypes.data,
+              cu_seqlens_dev=0x2000)
+    rc, ws = _walk(d)
+    assert rc == 0 and 1 <= ws <= 16
+    # the override, clamped to what the arithmetic allows
+    monkeypatch.setenv("LASP2_WALK_SLOTS", "3")
+    assert _walk(_desc(H=16, N=32768, **bf)) == (0, 3)
+    assert _walk(_desc(H=16, N=32768)) == (0, 1)
+    monkeypatch.setenv("LASP2_WALK_SLOTS", "0")
+    assert _walk(_desc(H=16, N=32768, **bf)) == (0, 4)
+    out = ctypes.c_int64(0)
+    assert B.lib().lasp2_walk_slots(None, 0, ctypes.byref(out)) == -1
+    assert B.lib().lasp2_walk_slots(ctypes.byref(_desc()), 0, None) == -1
+
+
 def test_workspace_size():
     out = ctypes.c_size_t(0)
     d = _desc(B=8, H=32, N=8192, d=128, C=256, dtype=B.LASP2_BF16)

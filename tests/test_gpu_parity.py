@@ -109,6 +109,34 @@ def test_many_documents(oracle, dtype, d, C, L, ndocs):
     _run_all(oracle, 1, 2, int(cu[-1]), d, C, L, dtype, seed=45, cu=cu)
 
 
+@pytest.mark.parametrize("ws", [2, 3, 5, 64])
+def test_walks_of_several_slots(oracle, monkeypatch, ws):
+    """The bf16 d = 128 attention kernels walk `ws` of the caller's slots per workgroup (forced here; by
+    itself the library does so only for launches of more walks than the device runs at once).  The
+    prefix array is then read at every ws-th slot of a document only, the backward builds its suffix
+    states per walk, and nothing else changes: ragged tails, more than one head and batch row, slots
+    shorter than the 128-row kernel's limit, packed documents of one and of many slots."""
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    monkeypatch.setenv("LASP2_WALK_SLOTS", str(ws))
+    p = bd.Problem(2, 2, 2304 + 77, 128, 256, 256, "bf16")
+    assert bd.lasp2_walk_slots(p) == ws and bd.lasp2_walk_slots(p, backward=True) == ws
+    _run_all(oracle, 2, 2, 2304 + 77, 128, 256, 256, "bf16", seed=70 + ws)
+    _run_all(oracle, 1, 3, 1000, 128, 64, 64, "bf16", seed=80 + ws)
+    _run_all(oracle, 1, 2, 1500, 128, 50, 100, "bf16", seed=90 + ws)
+    lens = [64, 700, 1, 255, 256, 257, 1467, 3, 2048]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _run_all(oracle, 1, 2, int(cu[-1]), 128, 128, 128, "bf16", seed=100 + ws, cu=cu)
+    rng = np.random.default_rng(ws)
+    lens = rng.integers(1, 400, size=70)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _run_all(oracle, 1, 2, int(cu[-1]), 128, 64, 64, "bf16", seed=110 + ws, cu=cu)
+    # the fp32 path keeps one walk per slot whatever the variable says
+    p32 = bd.Problem(1, 2, 1024, 64, 128, 128, "f32")
+    assert bd.lasp2_walk_slots(p32) == 1
+    _run_all(oracle, 1, 2, 1024, 64, 128, 128, "f32", seed=120 + ws)
+
+
 @pytest.mark.parametrize("decay", [False, True])
 def test_slot_lengths_around_block_and_half_boundaries(oracle, decay):
     """One slot per document, lengths on both sides of every 64-token block boundary of the 256-row
