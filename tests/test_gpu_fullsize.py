@@ -117,6 +117,21 @@ def test_cfg3_long_sequence_bench_configuration(oracle, first_head):
     _check_rows_and_states(oracle, "cfg3", first_head + 5, 32, rng)
 
 
+def test_walk_choices_of_the_named_workloads():
+    """What the library does with the named workloads on this device (one state per chunk in configs 2, 4
+    and 5 still gives long walks; config 3's 4 096-token slots are walked one by one) - the paths the
+    tests in this file then compare with the oracle."""
+    from paper_2502_07563_amd import binding as bd
+    want = {"cfg2": (4, 8), "cfg3": (1, 1), "cfg4": (32, 32)}
+    for name, (f, b) in want.items():
+        cfg = synth.CONFIGS[name]
+        p = bd.Problem(*(cfg[k] for k in ("B", "H", "N", "d", "C", "L", "dtype")), synth.config_offsets(cfg))
+        assert (bd.lasp2_walk_slots(p), bd.lasp2_walk_slots(p, backward=True)) == (f, b), name
+    cfg = synth.CONFIGS["cfg5"]
+    p = bd.Problem(*(cfg[k] for k in ("B", "H", "N", "d", "C", "L", "dtype")), synth.config_offsets(cfg))
+    assert bd.lasp2_walk_slots(p) > 1 and bd.lasp2_walk_slots(p, backward=True) > 1
+
+
 def test_cfg4_llama8b_layer(oracle):
     """B=8, H=32: 32 of the 256 (batch, head) groups in full, every batch row and every head index
     among them."""
