@@ -207,6 +207,16 @@ def test_random_shapes_bf16_d128(oracle, seed):
     _run_all(oracle, B, H, N, 128, C, L, "bf16", seed=200 + seed, cu=cu)
 
 
+@pytest.mark.parametrize("seed", range(10, 20))
+def test_random_shapes_and_walk_lengths_bf16_d128(oracle, monkeypatch, seed):
+    """The same draws of sizes with a drawn number of slots per walk forced on the attention kernels."""
+    B, H, N, C, L, cu = _random_case(seed)
+    ws = int(np.random.default_rng(seed).choice([2, 3, 4, 7, 32]))
+    print((B, H, N, C, L, None if cu is None else cu.tolist(), ws), flush=True)
+    monkeypatch.setenv("LASP2_WALK_SLOTS", str(ws))
+    _run_all(oracle, B, H, N, 128, C, L, "bf16", seed=220 + seed, cu=cu)
+
+
 def test_prefix_in_place_and_deterministic(oracle):
     import torch
     from paper_2502_07563_amd import binding as bd
