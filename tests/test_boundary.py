@@ -76,8 +76,8 @@ def test_walk_slots_choice(monkeypatch):
     as the device can keep busy; fp32, and slots that already hold a whole sequence, stay as they are."""
     monkeypatch.delenv("LASP2_WALK_SLOTS", raising=False)
     bf = dict(d=128, C=256, dtype=B.LASP2_BF16)
-    # 16 heads x 32 768 tokens, one state per chunk: walks of about 2 048 (forward) / 4 096 (backward)
-    # tokens, halved until the launch has two rounds of workgroups (256 forward walks at a time, 128
+    # 16 heads x 32 768 tokens, one state per chunk: walks of about 2 048 (forward) / 16 384 (backward;
+    # 4 096 in packed batches) tokens, halved until the launch has two rounds of workgroups (256 forward walks at a time, 128
     # backward ones, which take two workgroups each)
     assert _walk(_desc(H=16, N=32768, **bf)) == (0, 4)
     assert _walk(_desc(H=16, N=32768, **bf), 1) == (0, 8)
@@ -88,7 +88,9 @@ def test_walk_slots_choice(monkeypatch):
     assert _walk(_desc(B=10, H=30, N=8192, **bf)) == (0, 8)
     # 16 heads x 262 144 tokens in 4 096-token slots: long enough as they are
     assert _walk(_desc(H=16, N=262144, L=4096, **bf)) == (0, 1)
-    assert _walk(_desc(H=16, N=262144, L=4096, **bf), 1) == (0, 1)
+    # ... for the forward; the backward, which builds its states per walk, takes four of them
+    # (16 384 tokens, two rounds of 128 walks)
+    assert _walk(_desc(H=16, N=262144, L=4096, **bf), 1) == (0, 4)
     # a launch the device runs in one go stays as it is
     assert _walk(_desc(H=2, N=4096, **bf)) == (0, 1)
     # fp32 takes the plain kernels: one walk per slot

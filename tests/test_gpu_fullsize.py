@@ -119,10 +119,11 @@ def test_cfg3_long_sequence_bench_configuration(oracle, first_head):
 
 def test_walk_choices_of_the_named_workloads():
     """What the library does with the named workloads on this device (one state per chunk in configs 2, 4
-    and 5 still gives long walks; config 3's 4 096-token slots are walked one by one) - the paths the
+    and 5 still gives long walks; config 3's 4 096-token slots are walked one by one forwards, four at a
+    time backwards) - the paths the
     tests in this file then compare with the oracle."""
     from paper_2502_07563_amd import binding as bd
-    want = {"cfg2": (4, 8), "cfg3": (1, 1), "cfg4": (32, 32)}
+    want = {"cfg2": (4, 8), "cfg3": (1, 4), "cfg4": (32, 32)}
     for name, (f, b) in want.items():
         cfg = synth.CONFIGS[name]
         p = bd.Problem(*(cfg[k] for k in ("B", "H", "N", "d", "C", "L", "dtype")), synth.config_offsets(cfg))
