@@ -33,8 +33,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 #   mfma_insts_*:    v_mfma_f32_32x32x16_bf16 instructions per launch, SQ_INSTS_MFMA
 #                    (profiles/attn_kernels_cfg3_sq_counters.txt)
 PROFILE_CONSTANTS = {
-    "cfg3": {"traffic_fwd_bytes": 4.3626e9, "traffic_bwd_bytes": 7.7475e9,
-             "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 32636928},
+    "cfg3": {"traffic_fwd_bytes": 4.3626e9, "traffic_bwd_bytes": 7.6922e9,
+             "mfma_insts_fwd": 13500416, "mfma_insts_bwd": 32538624},
 }
 MFMA_FLOP = 2 * 32 * 32 * 16    # one v_mfma_f32_32x32x16_bf16
 
