@@ -382,7 +382,12 @@ def main():
         "roofline": {"bound": "hbm", "kernel": f"{which}: the longer of the step's two attention launches",
                      "achieved": head["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["frac"], "traffic": head["traffic"],
-                     "launch_ms": head["ms"], "launches": {"fwd": dict(lf, kernel=kern_fwd), "bwd": dict(lb, kernel=kern_bwd)},
+                     "launch_ms": head["ms"],
+                     "launches": {"fwd": dict(lf, kernel=kern_fwd),
+                                  "bwd": dict(lb, kernel=kern_bwd,
+                                              **({"note": "priced against HBM as the contract asks; what limits this launch "
+                                                          "is the LDS instruction rate inside its fused dV/dK workgroups"}
+                                                 if pair_kernel else {}))},
                      "device_copy_GBps": copy_gbps},
     }
     if graph_ms is not None:
