@@ -147,9 +147,10 @@ int lasp2_num_slots(const lasp2_desc_t* desc, int64_t* T_s);
  */
 int lasp2_walk_slots(const lasp2_desc_t* desc, int backward, int64_t* slots_per_walk);
 
-/* Bytes of device scratch lasp2_attn_bwd and lasp2_nomask_bwd need: one fp32 state array
- * [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine, followed by one 32-bit
- * counter per (b,h,slot) with which the backward's workgroups that read the same slot keep in
+/* Bytes of device scratch lasp2_attn_bwd and lasp2_nomask_bwd need: room for one fp32 state
+ * array [B,H,T_s,d,d] that holds dM_t and then, in place, its suffix combine (lasp2_attn_bwd
+ * may build fewer states than that: one per walk, see lasp2_walk_slots), followed by one 32-bit
+ * counter per (b,h,slot) with which the backward's workgroups that read the same tokens keep in
  * step (a matter of speed only: no result depends on a counter). */
 int lasp2_workspace_size(const lasp2_desc_t* desc, size_t* bytes);
 
