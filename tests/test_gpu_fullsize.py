@@ -153,6 +153,53 @@ def test_cfg5_packed_documents(oracle, first_head):
     _check_rows_and_states(oracle, "cfg5", first_head + 7, 32, rng)
 
 
+def test_tensors_beyond_4_gib_and_2_31_elements(oracle):
+    """Maximum sizes: 20 heads of 1 048 576 tokens make every [B,H,N,d] tensor 5 GiB and 2.7e9 elements, so
+    the last heads lie beyond byte offset 2^32 and element offset 2^31 (config 3's tensors are 1 GiB).  The
+    first and the last head are compared in full with the fp64 recurrence; inputs are drawn on the device
+    by torch's seeded generator and rounded to bf16 there, and exactly those values go to the oracle."""
+    import math
+    import torch
+    from paper_2502_07563_amd import binding as bd
+    _CACHE.clear()
+    torch.cuda.empty_cache()
+    B, H, N, d, C, L = 1, 20, 1 << 20, 128, 256, 4096
+    p = bd.Problem(B, H, N, d, C, L, "bf16")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20250207)
+
+    def draw():
+        t = torch.empty((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+        for h in range(H):      # head by head: the fp32 draw of a whole tensor would be 10 GiB
+            t[0, h] = (torch.randn((N, d), generator=gen, device="cuda") / math.sqrt(d)).to(torch.bfloat16)
+        return t
+    Q, K, V, dO = draw(), draw(), draw(), draw()
+    assert Q.numel() > 2 ** 31 and Q.numel() * 2 > 2 ** 32
+    nan = lambda t: t.fill_(float("nan"))
+    M = nan(bd.alloc_states(p))
+    P = nan(torch.empty_like(M))
+    O, dQ, dK, dV = (nan(torch.empty_like(Q)) for _ in range(4))
+    bd.lasp2_chunk_states(p, K, V, M)
+    bd.lasp2_state_prefix(p, M, P, False)
+    bd.lasp2_attn_fwd(p, Q, K, V, P, O)
+    bd.lasp2_attn_bwd(p, Q, K, V, dO, P, dQ, dK, dV, nan(bd.alloc_workspace(p)))
+    torch.cuda.synchronize()
+    groups = [0, H - 1]
+    host = lambda t: t[0, groups].float().cpu().numpy().astype(np.float64)
+    x = {n: host(t) for n, t in (("Q", Q), ("K", K), ("V", V), ("dO", dO))}
+    ref = {"O": oracle.fwd_rec(x["Q"], x["K"], x["V"])}
+    ref["dQ"], ref["dK"], ref["dV"] = oracle.bwd_rec(x["Q"], x["K"], x["V"], x["dO"])
+    del x
+    for k, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        whole, blk = assert_close_blocks(f"5 GiB tensors, {k}, heads 0 and {H - 1}", host(t), ref.pop(k), TOL["bf16"])
+        print(k, f"{whole:.2e} {blk:.2e}", flush=True)
+    # nothing was left unwritten anywhere else either
+    for t in (O, dQ, dK, dV):
+        assert not bool(torch.isnan(t[0, 1:H - 1].float().sum(dim=(-1, -2))).any())
+    del Q, K, V, dO, O, dQ, dK, dV, M, P
+    torch.cuda.empty_cache()
+
+
 def test_release_fullsize_cache():
     """Frees the device results the cases above shared before the remaining tests allocate theirs."""
     import torch
