@@ -282,6 +282,12 @@ def test_runs_on_the_callers_stream(oracle):
         assert torch.equal(a, b)
 
 
+def test_maximum_number_of_groups(oracle):
+    """B * H = 65 535 (the limit the descriptor check allows) short sequences: one workgroup per group in
+    every launch, the last groups at the far end of the one-dimensional grids."""
+    _run_all(oracle, 257, 255, 40, 128, 32, 32, "bf16", seed=77)
+
+
 def test_many_slots_not_multiple_of_eight(oracle):
     """Slot counts that do not fill the last group of eight workgroups of a launch."""
     _run_all(oracle, 1, 1, 256 * 11 + 70, 128, 256, 256, "bf16", seed=71)
